@@ -1,0 +1,23 @@
+"""CPU oracle of the compressed CDC shuffle (test infrastructure only).
+
+Nothing in the GPU product path may import this package; it exists so that
+tests, the smoke check and the benchmark's CPU-baseline leg have an
+independent answer to compare with.
+"""
+from .ccdc_oracle import (  # noqa: F401
+    OraclePlan,
+    build_library,
+    build_plan,
+    closed_form_elems,
+    combine,
+    decode,
+    direct,
+    encode,
+    label_rank,
+    packet_len,
+    reduce,
+    run_all,
+    scheduled_elems,
+    segment_count,
+    segment_len,
+)

@@ -1,0 +1,283 @@
+/*
+ * Oracle for the compressed CDC shuffle: placement, round schedule and byte
+ * counts.  The stage arithmetic lives in ccdc_oracle_stages.inc.
+ * Test infrastructure only (see ccdc_oracle.h): plain, single-threaded,
+ * unoptimised on purpose, and independent of the GPU library.
+ */
+#include "ccdc_oracle.h"
+
+#include <stdlib.h>
+#include <string.h>
+
+int64_t orc_binom(int n, int k)
+{
+    if (n < 0 || k < 0 || k > n) return -1;
+    if (k > n - k) k = n - k;
+    int64_t v = 1;
+    for (int i = 1; i <= k; i++) {
+        /* v = v * (n-k+i) / i stays integral at every step */
+        const int64_t f = n - k + i;
+        if (v > INT64_MAX / f) return -1;
+        v = v * f / i;
+    }
+    return v;
+}
+
+/* Advance the ascending k-subset s of {0..n-1} to its lexicographic successor.
+ * Returns 0 when s was the last one. */
+static int next_subset(int *s, int k, int n)
+{
+    int i = k - 1;
+    while (i >= 0 && s[i] == n - k + i) i--;
+    if (i < 0) return 0;
+    s[i]++;
+    for (int j = i + 1; j < k; j++) s[j] = s[j - 1] + 1;
+    return 1;
+}
+
+/* All k-subsets of {0..n-1}, ascending inside, lexicographic across: [count][k]. */
+static int *all_subsets(int n, int k, int64_t count)
+{
+    int *out = (int *)malloc(sizeof(int) * (size_t)count * (size_t)k);
+    int *s = (int *)malloc(sizeof(int) * (size_t)k);
+    if (!out || !s) { free(out); free(s); return NULL; }
+    for (int i = 0; i < k; i++) s[i] = i;
+    int64_t idx = 0;
+    do {
+        memcpy(out + idx * k, s, sizeof(int) * (size_t)k);
+        idx++;
+    } while (next_subset(s, k, n));
+    free(s);
+    return (idx == count) ? out : (free(out), (int *)NULL);
+}
+
+static int cmp_width;   /* single-threaded program: comparator width for bsearch */
+static int cmp_subset(const void *a, const void *b)
+{
+    const int *x = (const int *)a, *y = (const int *)b;
+    for (int i = 0; i < cmp_width; i++)
+        if (x[i] != y[i]) return x[i] < y[i] ? -1 : 1;
+    return 0;
+}
+
+/* Position of subset s in the lexicographically sorted table. */
+static int64_t find_subset(const int *table, int64_t count, int k, const int *s)
+{
+    cmp_width = k;
+    const int *hit = (const int *)bsearch(s, table, (size_t)count, sizeof(int) * (size_t)k, cmp_subset);
+    return hit ? (hit - table) / k : -1;
+}
+
+/* dst = src without its element at position skip. */
+static void drop_member(const int *src, int len, int skip, int *dst)
+{
+    for (int i = 0, j = 0; i < len; i++)
+        if (i != skip) dst[j++] = src[i];
+}
+
+static int is_permutation(const int *order, int64_t len)
+{
+    char *seen = (char *)calloc((size_t)len, 1);
+    if (!seen) return 0;
+    int ok = 1;
+    for (int64_t i = 0; i < len && ok; i++) {
+        if (order[i] < 0 || order[i] >= len || seen[order[i]]) ok = 0;
+        else seen[order[i]] = 1;
+    }
+    free(seen);
+    return ok;
+}
+
+void orc_plan_free(orc_plan *p)
+{
+    if (!p) return;
+    free(p->batch_job); free(p->batch_file0); free(p->batch_label);
+    free(p->round_member); free(p->round_batch);
+    free(p);
+}
+
+orc_plan *orc_plan_build(int K, int r, int Q, int N, int schedule, const int *batch_order, int order_sets)
+{
+    /* Sec. III, network model: K | Q, K <= N; Theorem 1: mu*K in {1..K-1}. */
+    if (K < 2 || r < 1 || r > K - 1 || Q < 1 || N < 1 || Q % K != 0 || K > N) return NULL;
+    if (schedule != ORC_SINGLE_JOB && schedule != ORC_PAPER_JOBS) return NULL;
+    const int r1 = r + 1;
+    const int64_t n_lab = orc_binom(K, r);     /* r-subsets: batch labels */
+    const int64_t G = orc_binom(K, r1);        /* (r+1)-subsets: shuffle subsets */
+    if (n_lab < 0 || G < 0 || n_lab > INT32_MAX || G > INT32_MAX) return NULL;
+
+    const int64_t per_job = (schedule == ORC_SINGLE_JOB) ? n_lab : r1;
+    if (N % per_job != 0) return NULL;
+    const int64_t n_jobs = (schedule == ORC_SINGLE_JOB) ? 1 : G;
+    if (batch_order) {
+        if (order_sets != 1 && order_sets != n_jobs) return NULL;
+        for (int s = 0; s < order_sets; s++)
+            if (!is_permutation(batch_order + s * per_job, per_job)) return NULL;
+    }
+
+    orc_plan *p = (orc_plan *)calloc(1, sizeof(orc_plan));
+    int *labels = all_subsets(K, r, n_lab);
+    int *groups = all_subsets(K, r1, G);
+    int *tmp = (int *)malloc(sizeof(int) * (size_t)(r1 + 1));
+    if (!p || !labels || !groups || !tmp) goto fail;
+
+    p->K = K; p->r = r; p->Q = Q; p->N = N; p->c = Q / K;
+    p->m = (int)(N / per_job);
+    if (schedule == ORC_SINGLE_JOB) {
+        p->J = 1; p->n_batch = n_lab; p->n_round = G;
+    } else {
+        if (G * (int64_t)(K - r) > INT32_MAX) goto fail;
+        p->J = (int)G; p->n_batch = G * r1; p->n_round = G * (K - r);
+    }
+    p->batch_job = (int *)malloc(sizeof(int) * (size_t)p->n_batch);
+    p->batch_file0 = (int *)malloc(sizeof(int) * (size_t)p->n_batch);
+    p->batch_label = (int *)malloc(sizeof(int) * (size_t)p->n_batch * (size_t)r);
+    p->round_member = (int *)malloc(sizeof(int) * (size_t)p->n_round * (size_t)r1);
+    p->round_batch = (int *)malloc(sizeof(int) * (size_t)p->n_round * (size_t)r1);
+    if (!p->batch_job || !p->batch_file0 || !p->batch_label || !p->round_member || !p->round_batch) goto fail;
+
+    if (schedule == ORC_SINGLE_JOB) {
+        /* Placement of Sec. IV-A with the whole cluster in the role of K_j: the
+         * files are cut into one batch per r-subset P, batch P is stored on the
+         * nodes of P. */
+        for (int64_t pr = 0; pr < n_lab; pr++) {
+            p->batch_job[pr] = 0;
+            p->batch_file0[pr] = (batch_order ? batch_order[pr] : (int)pr) * p->m;
+            memcpy(p->batch_label + pr * r, labels + pr * r, sizeof(int) * (size_t)r);
+        }
+        /* One stage-1 round (Sec. IV-B) in every (r+1)-subset S: member s_b is
+         * served the batch labelled S minus s_b. */
+        for (int64_t u = 0; u < G; u++) {
+            const int *S = groups + u * r1;
+            memcpy(p->round_member + u * r1, S, sizeof(int) * (size_t)r1);
+            for (int b = 0; b < r1; b++) {
+                drop_member(S, r1, b, tmp);
+                const int64_t bt = find_subset(labels, n_lab, r, tmp);
+                if (bt < 0) goto fail;
+                p->round_batch[u * r1 + b] = (int)bt;
+            }
+        }
+    } else {
+        /* Sec. IV-A: job j is placed on the j-th (r+1)-subset K_j; its files are
+         * cut into r+1 batches labelled by the r-subsets of K_j (taken here in
+         * lexicographic order, i.e. dropping s_r first, s_0 last). */
+        for (int64_t j = 0; j < G; j++) {
+            const int *Kj = groups + j * r1;
+            for (int pr = 0; pr < r1; pr++) {
+                const int64_t bt = j * r1 + pr;
+                p->batch_job[bt] = (int)j;
+                const int *order = batch_order ? batch_order + (order_sets == 1 ? 0 : j * r1) : NULL;
+                p->batch_file0[bt] = (order ? order[pr] : pr) * p->m;
+                drop_member(Kj, r1, r - pr, p->batch_label + bt * r);
+            }
+        }
+        int64_t u = 0;
+        for (int64_t j = 0; j < G; j++) {
+            const int *Kj = groups + j * r1;
+            /* Stage 1 (Sec. IV-B): job j inside its own subset. */
+            memcpy(p->round_member + u * r1, Kj, sizeof(int) * (size_t)r1);
+            for (int b = 0; b < r1; b++)
+                p->round_batch[u * r1 + b] = (int)(j * r1 + (r - b));   /* label K_j minus s_b */
+            u++;
+            /* Stage 2 (Sec. IV-B): for every node i outside K_j, member s_b is
+             * served the batch labelled K_j minus s_b of the job that lives on
+             * {i} union K_j minus s_b. */
+            for (int i = 0; i < K; i++) {
+                int inside = 0;
+                for (int b = 0; b < r1; b++) inside |= (Kj[b] == i);
+                if (inside) continue;
+                memcpy(p->round_member + u * r1, Kj, sizeof(int) * (size_t)r1);
+                for (int b = 0; b < r1; b++) {
+                    /* tmp = sorted({i} union K_j minus s_b); pos = where i landed */
+                    drop_member(Kj, r1, b, tmp);
+                    int pos = r;
+                    while (pos > 0 && tmp[pos - 1] > i) { tmp[pos] = tmp[pos - 1]; pos--; }
+                    tmp[pos] = i;
+                    const int64_t jb = find_subset(groups, G, r1, tmp);
+                    if (jb < 0) goto fail;
+                    /* in job jb the wanted label is its subset minus i, i.e. the
+                     * batch that drops position pos */
+                    p->round_batch[u * r1 + b] = (int)(jb * r1 + (r - pos));
+                }
+                u++;
+            }
+        }
+        if (u != p->n_round) goto fail;
+    }
+    free(labels); free(groups); free(tmp);
+    return p;
+fail:
+    free(labels); free(groups); free(tmp);
+    orc_plan_free(p);
+    return NULL;
+}
+
+/* Sec. IV-B says the packet is split evenly into r segments and silently
+ * assumes r | W.  Reading used here: if 4r | W the split is exact; otherwise
+ * ell = ceil(W/r) rounded up to a multiple of 4 elements, segment rho covers
+ * [rho*ell, min(W,(rho+1)*ell)) and the last segments may be short or empty. */
+int64_t orc_segment_len(int64_t W, int r)
+{
+    const int64_t A = 4;
+    if (W % (r * A) == 0) return W / r;
+    const int64_t q = (W + r - 1) / r;
+    return (q + A - 1) / A * A;
+}
+
+int64_t orc_segment_count(int64_t W, int r, int rho)
+{
+    const int64_t ell = orc_segment_len(W, r);
+    const int64_t lo = rho * ell;
+    if (lo >= W) return 0;
+    const int64_t hi = (lo + ell < W) ? lo + ell : W;
+    return hi - lo;
+}
+
+int orc_label_rank(int a, int b)
+{
+    return a > b ? a - 1 : a;
+}
+
+int64_t orc_packet_len(int64_t W, int r, int a)
+{
+    int64_t len = 0;
+    for (int b = 0; b <= r; b++) {
+        if (b == a) continue;
+        const int64_t n = orc_segment_count(W, r, orc_label_rank(a, b));
+        if (n > len) len = n;
+    }
+    return len;
+}
+
+int64_t orc_scheduled_elems(const orc_plan *p, int64_t T)
+{
+    const int64_t W = (int64_t)p->c * T;
+    int64_t per_round = 0;
+    for (int a = 0; a <= p->r; a++) per_round += orc_packet_len(W, p->r, a);
+    return per_round * p->n_round;
+}
+
+#define CAT2(a, b) a##b
+#define CAT(a, b) CAT2(a, b)
+
+#define FN(name) CAT(name, _f64)
+#define TIN float
+#define TEL double
+#define ZERO 0.0
+#define ADD(a, b) ((a) + (b))
+#define SUB(a, b) ((a) - (b))
+#include "ccdc_oracle_stages.inc"
+#undef FN
+#undef TIN
+#undef TEL
+#undef ZERO
+#undef ADD
+#undef SUB
+
+#define FN(name) CAT(name, _u32)
+#define TIN uint32_t
+#define TEL uint32_t
+#define ZERO 0u
+#define ADD(a, b) ((a) ^ (b))
+#define SUB(a, b) ((a) ^ (b))
+#include "ccdc_oracle_stages.inc"

@@ -1,0 +1,238 @@
+"""ctypes binding of the C oracle (test infrastructure only).
+
+Argument marshalling only: every number comes out of ccdc_oracle.c.  The
+shared object is built with gcc next to the sources; nothing here touches the
+GPU library.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from fractions import Fraction
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SO = os.path.join(_HERE, "libccdc_oracle.so")
+_SRCS = ["ccdc_oracle.c"]
+_DEPS = ["ccdc_oracle.c", "ccdc_oracle.h", "ccdc_oracle_stages.inc"]
+
+
+def build_library(force: bool = False) -> str:
+    """Compile the oracle with gcc (-O2, single thread) if missing or stale."""
+    stale = force or not os.path.exists(_SO)
+    if not stale:
+        so_time = os.path.getmtime(_SO)
+        stale = any(os.path.getmtime(os.path.join(_HERE, d)) > so_time for d in _DEPS)
+    if stale:
+        cmd = ["gcc", "-std=c11", "-O2", "-Wall", "-Wextra", "-fPIC", "-shared",
+               "-o", _SO] + [os.path.join(_HERE, s) for s in _SRCS]
+        subprocess.run(cmd, check=True, cwd=_HERE)
+    return _SO
+
+
+class _CPlan(C.Structure):
+    _fields_ = [
+        ("K", C.c_int), ("r", C.c_int), ("Q", C.c_int), ("N", C.c_int),
+        ("J", C.c_int), ("c", C.c_int), ("m", C.c_int),
+        ("n_batch", C.c_int64), ("n_round", C.c_int64),
+        ("batch_job", C.POINTER(C.c_int)),
+        ("batch_file0", C.POINTER(C.c_int)),
+        ("batch_label", C.POINTER(C.c_int)),
+        ("round_member", C.POINTER(C.c_int)),
+        ("round_batch", C.POINTER(C.c_int)),
+    ]
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    lib = C.CDLL(build_library())
+    P = C.POINTER(_CPlan)
+    lib.orc_binom.restype = C.c_int64
+    lib.orc_binom.argtypes = [C.c_int, C.c_int]
+    lib.orc_plan_build.restype = P
+    lib.orc_plan_build.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_int), C.c_int]
+    lib.orc_plan_free.restype = None
+    lib.orc_plan_free.argtypes = [P]
+    lib.orc_segment_len.restype = C.c_int64
+    lib.orc_segment_len.argtypes = [C.c_int64, C.c_int]
+    lib.orc_segment_count.restype = C.c_int64
+    lib.orc_segment_count.argtypes = [C.c_int64, C.c_int, C.c_int]
+    lib.orc_label_rank.restype = C.c_int
+    lib.orc_label_rank.argtypes = [C.c_int, C.c_int]
+    lib.orc_packet_len.restype = C.c_int64
+    lib.orc_packet_len.argtypes = [C.c_int64, C.c_int, C.c_int]
+    lib.orc_scheduled_elems.restype = C.c_int64
+    lib.orc_scheduled_elems.argtypes = [P, C.c_int64]
+    vp = C.c_void_p
+    for sfx in ("f64", "u32"):
+        for name, nptr in (("combine", 2), ("encode", 2), ("decode", 3), ("reduce", 3), ("direct", 2)):
+            fn = getattr(lib, f"orc_{name}_{sfx}")
+            fn.restype = None
+            fn.argtypes = [P, C.c_int64] + [vp] * nptr
+    _lib = lib
+    return lib
+
+
+def _arr(ptr, shape):
+    n = int(np.prod(shape))
+    if n == 0:
+        return np.zeros(shape, dtype=np.int32)
+    return np.ctypeslib.as_array(ptr, shape=(n,)).reshape(shape).astype(np.int32, copy=True)
+
+
+class OraclePlan:
+    """Placement + round schedule as built by orc_plan_build (read-only copies)."""
+
+    def __init__(self, ptr):
+        self._ptr = ptr
+        s = ptr.contents
+        self.K, self.r, self.Q, self.N = s.K, s.r, s.Q, s.N
+        self.J, self.c, self.m = s.J, s.c, s.m
+        self.n_batch, self.n_round = int(s.n_batch), int(s.n_round)
+        self.batch_job = _arr(s.batch_job, (self.n_batch,))
+        self.batch_file0 = _arr(s.batch_file0, (self.n_batch,))
+        self.batch_label = _arr(s.batch_label, (self.n_batch, self.r))
+        self.round_member = _arr(s.round_member, (self.n_round, self.r + 1))
+        self.round_batch = _arr(s.round_batch, (self.n_round, self.r + 1))
+
+    def __del__(self):
+        try:
+            if self._ptr:
+                _load().orc_plan_free(self._ptr)
+                self._ptr = None
+        except Exception:
+            pass
+
+    # shapes of the artefacts for value length T
+    def W(self, T):
+        return self.c * T
+
+    def shapes(self, T):
+        W = self.c * T
+        ell = segment_len(W, self.r)
+        R, r1 = self.n_round, self.r + 1
+        return {"V": (self.J, self.N, self.Q, T), "Vbar": (R, r1, W), "X": (R, r1, ell),
+                "D": (R, r1, W), "Phi": (self.J, self.Q, T)}
+
+
+def build_plan(K, r, Q, N, schedule="single", batch_order=None):
+    """schedule: "single" (one job, one batch per r-subset) or "paper" (J=C(K,r+1) jobs).
+
+    batch_order: one permutation (shared) or a list of J permutations (one per job)."""
+    lib = _load()
+    sched = {"single": 0, "paper": 1}[schedule]
+    order, sets = None, 0
+    if batch_order is not None:
+        rows = np.atleast_2d(np.asarray(batch_order, dtype=np.int32))   # one row per permutation
+        sets = rows.shape[0]
+        order = (C.c_int * rows.size)(*[int(v) for v in rows.ravel()])
+    ptr = lib.orc_plan_build(K, r, Q, N, sched, order, sets)
+    if not ptr:
+        raise ValueError(f"invalid parameters K={K} r={r} Q={Q} N={N} schedule={schedule}")
+    return OraclePlan(ptr)
+
+
+def segment_len(W, r):
+    return int(_load().orc_segment_len(W, r))
+
+
+def segment_count(W, r, rho):
+    return int(_load().orc_segment_count(W, r, rho))
+
+
+def label_rank(a, b):
+    return int(_load().orc_label_rank(a, b))
+
+
+def packet_len(W, r, a):
+    return int(_load().orc_packet_len(W, r, a))
+
+
+def scheduled_elems(plan, T):
+    return int(_load().orc_scheduled_elems(plan._ptr, T))
+
+
+def closed_form_elems(plan, T):
+    """Per round (r+1) packets of c*T/r elements each (Sec. IV-B load analysis)."""
+    return Fraction((plan.r + 1) * plan.c * T, plan.r) * plan.n_round
+
+
+def _mode(a):
+    if a.dtype == np.uint32:
+        return "u32", np.uint32
+    if a.dtype in (np.float32, np.float64):
+        return "f64", np.float64
+    raise TypeError(f"unsupported dtype {a.dtype}")
+
+
+def _ptr(a):
+    return a.ctypes.data_as(C.c_void_p)
+
+
+def _check(a, dtype, shape, name):
+    if a.dtype != dtype or not a.flags.c_contiguous or tuple(a.shape) != tuple(shape):
+        raise ValueError(f"{name}: want contiguous {np.dtype(dtype).name}{tuple(shape)}, "
+                         f"got {a.dtype}{tuple(a.shape)}")
+
+
+def combine(plan, T, V):
+    sfx, el = _mode(V)
+    sh = plan.shapes(T)
+    _check(V, np.float32 if sfx == "f64" else np.uint32, sh["V"], "V")
+    out = np.empty(sh["Vbar"], dtype=el)
+    getattr(_load(), f"orc_combine_{sfx}")(plan._ptr, T, _ptr(V), _ptr(out))
+    return out
+
+
+def encode(plan, T, Vbar):
+    sfx, el = _mode(Vbar)
+    sh = plan.shapes(T)
+    _check(Vbar, el, sh["Vbar"], "Vbar")
+    out = np.empty(sh["X"], dtype=el)
+    getattr(_load(), f"orc_encode_{sfx}")(plan._ptr, T, _ptr(Vbar), _ptr(out))
+    return out
+
+
+def decode(plan, T, X, Vbar):
+    sfx, el = _mode(Vbar)
+    sh = plan.shapes(T)
+    _check(X, el, sh["X"], "X")
+    _check(Vbar, el, sh["Vbar"], "Vbar")
+    out = np.zeros(sh["D"], dtype=el)
+    getattr(_load(), f"orc_decode_{sfx}")(plan._ptr, T, _ptr(X), _ptr(Vbar), _ptr(out))
+    return out
+
+
+def reduce(plan, T, V, D):
+    sfx, el = _mode(V)
+    sh = plan.shapes(T)
+    _check(V, np.float32 if sfx == "f64" else np.uint32, sh["V"], "V")
+    _check(D, el, sh["D"], "D")
+    out = np.empty(sh["Phi"], dtype=el)
+    getattr(_load(), f"orc_reduce_{sfx}")(plan._ptr, T, _ptr(V), _ptr(D), _ptr(out))
+    return out
+
+
+def direct(plan, T, V):
+    sfx, el = _mode(V)
+    sh = plan.shapes(T)
+    _check(V, np.float32 if sfx == "f64" else np.uint32, sh["V"], "V")
+    out = np.empty(sh["Phi"], dtype=el)
+    getattr(_load(), f"orc_direct_{sfx}")(plan._ptr, T, _ptr(V), _ptr(out))
+    return out
+
+
+def run_all(plan, T, V):
+    """All four stages in order; returns every artefact."""
+    Vbar = combine(plan, T, V)
+    X = encode(plan, T, Vbar)
+    D = decode(plan, T, X, Vbar)
+    Phi = reduce(plan, T, V, D)
+    return {"Vbar": Vbar, "X": X, "D": D, "Phi": Phi}

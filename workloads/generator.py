@@ -1,0 +1,86 @@
+"""Counter-based input generator: v_{q,n}[i] is a pure function of (seed, job, q, n, i).
+
+Recipe: h = splitmix64-finaliser(seed + GOLDEN * (1 + counter)) with
+counter = (((job*Q + q)*N + n)*T + i).  uint32 payload = top 32 bits of h.
+fp32 payload = Box-Muller on two 24-bit uniforms cut from h, evaluated in fp64
+and rounded once to fp32.  Output layout [J][N][Q][T] (file-major).
+
+Two backends produce the same recipe: numpy (host) and torch (any device).
+The uint32 payload is bit-identical across backends; the fp32 payload may
+differ in the last bit between backends (log/cos implementations), so a test
+always generates once and hands the same array to both sides.
+"""
+from __future__ import annotations
+
+import math
+
+import numpy as np
+
+_GOLDEN = 0x9E3779B97F4A7C15
+_M1 = 0xBF58476D1CE4E5B9
+_M2 = 0x94D049BB133111EB
+_MASK64 = (1 << 64) - 1
+
+
+def _mix64_np(z):
+    z = (z ^ (z >> np.uint64(30))) * np.uint64(_M1)
+    z = (z ^ (z >> np.uint64(27))) * np.uint64(_M2)
+    return z ^ (z >> np.uint64(31))
+
+
+def generate_numpy(J, N, Q, T, seed, mode, sigma=1.0):
+    """Host arrays: float32 (mode "f32") or uint32 (mode "u32"), shape (J, N, Q, T)."""
+    out = np.empty((J, N, Q, T), dtype=np.float32 if mode == "f32" else np.uint32)
+    i = np.arange(T, dtype=np.uint64)[None, :]
+    q = np.arange(Q, dtype=np.uint64)[:, None]
+    with np.errstate(over="ignore"):
+        for j in range(J):
+            for n in range(N):
+                ctr = ((np.uint64(j * Q) + q) * np.uint64(N) + np.uint64(n)) * np.uint64(T) + i
+                h = _mix64_np(np.uint64(seed & _MASK64) + np.uint64(_GOLDEN) * (np.uint64(1) + ctr))
+                if mode == "u32":
+                    out[j, n] = (h >> np.uint64(32)).astype(np.uint32)
+                else:
+                    u1 = ((h >> np.uint64(40)).astype(np.float64) + 1.0) / 16777216.0
+                    u2 = ((h >> np.uint64(16)) & np.uint64(0xFFFFFF)).astype(np.float64) / 16777216.0
+                    z = sigma * np.sqrt(-2.0 * np.log(u1)) * np.cos(2.0 * math.pi * u2)
+                    out[j, n] = z.astype(np.float32)
+    return out
+
+
+def _s64(x):
+    """Two's-complement reinterpretation of an unsigned 64-bit constant."""
+    x &= _MASK64
+    return x - (1 << 64) if x >= (1 << 63) else x
+
+
+def generate_torch(J, N, Q, T, seed, mode, sigma=1.0, device="cpu"):
+    """Same recipe with torch ops (int64 arithmetic wraps mod 2^64).
+
+    Returns float32 for "f32"; for "u32" returns an int32 tensor holding the
+    uint32 bit patterns (torch has no arithmetic uint32 type)."""
+    import torch
+
+    def lsr(z, s):
+        return (z >> s) & ((1 << (64 - s)) - 1)
+
+    def mix(z):
+        z = (z ^ lsr(z, 30)) * _s64(_M1)
+        z = (z ^ lsr(z, 27)) * _s64(_M2)
+        return z ^ lsr(z, 31)
+
+    out = torch.empty((J, N, Q, T), dtype=torch.float32 if mode == "f32" else torch.int32, device=device)
+    i = torch.arange(T, dtype=torch.int64, device=device)[None, :]
+    q = torch.arange(Q, dtype=torch.int64, device=device)[:, None]
+    for j in range(J):
+        for n in range(N):
+            ctr = ((j * Q + q) * N + n) * T + i
+            h = mix(_s64(seed) + _s64(_GOLDEN) * (1 + ctr))
+            if mode == "u32":
+                out[j, n] = lsr(h, 32).to(torch.int32)          # wraps: keeps the low 32 bits
+            else:
+                u1 = (lsr(h, 40).to(torch.float64) + 1.0) / 16777216.0
+                u2 = (lsr(h, 16) & 0xFFFFFF).to(torch.float64) / 16777216.0
+                z = sigma * torch.sqrt(-2.0 * torch.log(u1)) * torch.cos(2.0 * math.pi * u2)
+                out[j, n] = z.to(torch.float32)
+    return out
