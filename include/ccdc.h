@@ -1,0 +1,161 @@
+/*
+ * libccdc: the shuffle-stage packet pipeline of compressed coded distributed
+ * computing (pre-combine -> split + encode -> decode -> final reduction) for
+ * AMD CDNA4 (gfx950), with all K nodes of the cluster emulated on one GPU.
+ *
+ * Model and notation (paper, Sec. III and Sec. IV): K nodes, each file stored
+ * on r = mu*K nodes, Q output functions per job (K | Q, node k reduces the
+ * c = Q/K functions k*c .. k*c+c-1), N files per job, J jobs, intermediate
+ * values v_{q,n} of T elements.  W = c*T is the length of one concatenated
+ * pre-combined packet.  A "round" is one run of the shuffle steps of Sec. IV-B
+ * inside one subset S = {s_0 < ... < s_r} of r+1 nodes: member b is served the
+ * batch stored on the other r members.  All ids are 0-based.
+ *
+ * Buffers (row-major, 4-byte elements, DEVICE memory owned by the caller,
+ * 16-byte aligned for the vector path; sizes come from ccdc_plan_query):
+ *   V    [J][N][Q][T]     intermediate values, file-major
+ *   Vbar [R][r+1][W]      pre-combined packet of round u for member b
+ *   X    [R][r+1][ell]    coded packet of round u sent by member a; ell is
+ *                         the segment length, words past a sender's true
+ *                         packet length hold the zero of the algebra
+ *   D    [R][r+1][W]      packet decoded by member b in round u
+ *   Phi  [J][Q][T]        reduced outputs
+ * Subsets (batch labels and rounds) are numbered in lexicographic order.
+ * When r does not divide W the split "evenly into mu*K segments" (Sec. IV-B)
+ * is read as: ell = W/r if 4r | W, else ceil(W/r) rounded up to a multiple of
+ * 4; segment rho = [rho*ell, min(W,(rho+1)*ell)), the tail may be short/empty.
+ *
+ * Payload modes: CCDC_F32_SUM (fp32, real + to combine/encode/reduce, real -
+ * to decode) and CCDC_U32_XOR (uint32 words of the paper's field F_{2^T},
+ * + and - are both XOR; bit-exact).
+ *
+ * Every function returns CCDC_OK (0) or a negative ccdc_status; nothing is
+ * written to an output on error and the library never aborts or throws.
+ * Stage calls only enqueue kernels on `stream` (a hipStream_t passed as
+ * void*, NULL = the default stream) and allocate nothing; execution errors
+ * surface at the caller's next synchronisation.  A plan may be used from one
+ * stream at a time (its reduction workspace is shared between calls).
+ */
+#ifndef CCDC_H
+#define CCDC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ccdc_plan_s ccdc_plan_t;   /* opaque, owned by the library */
+
+enum ccdc_status {
+    CCDC_OK = 0,
+    CCDC_EINVAL = -1,    /* bad parameter, null pointer, misaligned or unknown enum */
+    CCDC_ENOMEM = -2,    /* host or device allocation failed */
+    CCDC_EHIP = -3,      /* a HIP runtime call failed (no device, bad launch) */
+    CCDC_ESIZE = -4,     /* a count exceeds what tables/kernels index (see ccdc_plan_bind) */
+    CCDC_ESTATE = -5     /* plan not bound / not uploaded / wrong device for this call */
+};
+
+enum ccdc_mode { CCDC_F32_SUM = 0, CCDC_U32_XOR = 1 };
+
+/* Items for ccdc_plan_query.  Scalars are written as one int64_t; tables as
+ * arrays of the stated type and shape. */
+enum ccdc_query {
+    CCDC_Q_K = 0, CCDC_Q_R, CCDC_Q_Q, CCDC_Q_N, CCDC_Q_J, CCDC_Q_C, CCDC_Q_M,
+    CCDC_Q_NBATCH,           /* batches over all jobs */
+    CCDC_Q_NROUND,           /* rounds R */
+    CCDC_Q_T, CCDC_Q_MODE, CCDC_Q_W,                 /* need a bound plan from here on */
+    CCDC_Q_SEG_LEN,          /* ell */
+    CCDC_Q_SCHEDULED_ELEMS,  /* elements all coded packets really carry */
+    CCDC_Q_CLOSED_FORM_NUM,  /* R*(r+1)*c*T  (Sec. IV-B: r+1 packets of c*T/r per round) */
+    CCDC_Q_CLOSED_FORM_DEN,  /* r */
+    CCDC_Q_V_ELEMS, CCDC_Q_VBAR_ELEMS, CCDC_Q_X_ELEMS, CCDC_Q_D_ELEMS, CCDC_Q_PHI_ELEMS,
+    CCDC_Q_WORKSPACE_BYTES,  /* device bytes ccdc_plan_upload allocates besides tables */
+    CCDC_Q_PACKET_LEN = 64,  /* int64_t[r+1]      true packet length of sender a        */
+    CCDC_Q_BATCH_JOB,        /* int32_t[NBATCH]    job of the batch                     */
+    CCDC_Q_BATCH_FILE0,      /* int32_t[NBATCH]    first file (index inside its job)    */
+    CCDC_Q_BATCH_LABEL,      /* int32_t[NBATCH][r] nodes storing the batch, ascending   */
+    CCDC_Q_ROUND_MEMBER,     /* int32_t[R][r+1]    nodes of the round, ascending        */
+    CCDC_Q_ROUND_BATCH       /* int32_t[R][r+1]    batch served to member b             */
+};
+
+/*
+ * Placement and schedule, host only (no GPU needed).
+ * ccdc_plan: ONE job; its N files are cut into C(K,r) batches, batch p (files
+ *   [p*m,(p+1)*m), m = N/C(K,r)) is stored on the p-th r-subset of the K nodes
+ *   (placement of Sec. IV-A with the whole cluster as the job's subset), and
+ *   every (r+1)-subset runs one stage-1 round of Sec. IV-B.  R = C(K,r+1).
+ * ccdc_plan_jobs: the scheme as Sec. IV states it: J = C(K,r+1) jobs, job j on
+ *   the j-th (r+1)-subset in r+1 batches (m = N/(r+1)); each subset runs its
+ *   stage-1 round, then one stage-2 round per outside node in ascending order.
+ *   R = C(K,r+1)*(K-r).  Its load is Theorem 1's.
+ * Errors: CCDC_EINVAL for K<2, r<1, r>K-1 (Theorem 1: mu*K in 1..K-1), Q<1,
+ *   K not dividing Q or K>N (Sec. III network model), batch count not dividing
+ *   N (Sec. IV-A), null out; CCDC_ESIZE if a table would pass 2^31-1 entries.
+ * The plan is owned by the library; release it with ccdc_plan_destroy.
+ */
+int ccdc_plan(int K, int r, int Q, int N, ccdc_plan_t **out);
+int ccdc_plan_jobs(int K, int r, int Q, int N, ccdc_plan_t **out);
+void ccdc_plan_destroy(ccdc_plan_t *plan);   /* frees host and device parts; NULL is fine */
+
+/*
+ * Fix the value length T (elements) and the payload mode: computes W, the
+ * segment split (Sec. IV-B) and the traffic the schedule puts on the wire.
+ * Host only.  May be called again; that drops any device tables.
+ * Errors: CCDC_EINVAL (T<1, unknown mode), CCDC_ESIZE when a buffer would
+ * hold more than 2^40 elements or a kernel's work-item count would pass 2^31-1.
+ */
+int ccdc_plan_bind(ccdc_plan_t *plan, int64_t T, int mode);
+
+/*
+ * Copy the index tables to the CURRENT HIP device and allocate the reduction
+ * workspace there (the only device allocations the library ever makes).
+ * Needs a bound plan.  CCDC_EHIP / CCDC_ENOMEM on failure; the host side of
+ * the plan stays valid.
+ */
+int ccdc_plan_upload(ccdc_plan_t *plan);
+
+/* Read a scalar or copy a table (host memory).  CCDC_EINVAL on unknown item,
+ * null pointer or out_bytes smaller than the item; CCDC_ESTATE if the item
+ * needs ccdc_plan_bind first. */
+int ccdc_plan_query(const ccdc_plan_t *plan, int what, void *out, size_t out_bytes);
+
+const char *ccdc_strerror(int status);
+
+/*
+ * The four stages.  All pointers are device pointers; see the buffer table
+ * above for shapes.  Each needs an uploaded plan (CCDC_ESTATE otherwise) and
+ * the plan's device to be current.
+ */
+
+/* Pre-combining (Sec. IV-B): Vbar[u][b][e] = sum over the m files n of the
+ * batch served to member b of V[job][n][s_b*c*T + e]. */
+int ccdc_combine(const ccdc_plan_t *plan, const void *V, void *Vbar, void *stream);
+
+/* Split and encode (Sec. IV-B, coded-packet equation): sender a adds, over the
+ * other members b, the segment of Vbar[u][b] that carries a's label, i.e.
+ * segment rank(a,b) = a - [a>b]:  X[u][a][x] = sum_{b!=a} Vbar[u][b][rank*ell+x]. */
+int ccdc_encode(const ccdc_plan_t *plan, const void *Vbar, void *X, void *stream);
+
+/* Decode (Sec. IV-B): receiver b removes from X[u][a] the segments of the
+ * packets Vbar[u][b'], b' not in {a,b}, which it can compute itself because it
+ * stores their batches:  D[u][b][rank(a,b)*ell+x] = X[u][a][x] - sum Vbar[u][b'][rank(a,b')*ell+x].
+ * Row Vbar[u][b] (the packet being recovered) is never read for receiver b. */
+int ccdc_decode(const ccdc_plan_t *plan, const void *X, const void *Vbar, void *D, void *stream);
+
+/* Final reduction (Sec. IV-B, last paragraphs): Phi[job][k*c*T+e] = sum of V over
+ * the files node k stores itself (batch order) + sum of D[u][b] over the rounds
+ * in which k was member b (round order).  Uses the plan's workspace when the
+ * sum is split. */
+int ccdc_reduce(const ccdc_plan_t *plan, const void *V, const void *D, void *Phi, void *stream);
+
+/* combine + encode + decode in one pass: every needed element of V is read
+ * once, X and D are written; Vbar is never materialised.  Results equal the
+ * three separate calls (bit-exact in XOR mode; same operation order in fp32). */
+int ccdc_shuffle_fused(const ccdc_plan_t *plan, const void *V, void *X, void *D, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

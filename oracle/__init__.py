@@ -20,4 +20,5 @@ from .ccdc_oracle import (  # noqa: F401
     scheduled_elems,
     segment_count,
     segment_len,
+    select_rounds,
 )

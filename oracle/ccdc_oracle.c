@@ -212,6 +212,38 @@ fail:
     return NULL;
 }
 
+/* Copy of a plan that keeps all batches but only the listed rounds (in the
+ * given order); lets a test run the stages on a sample of a large schedule. */
+orc_plan *orc_plan_select_rounds(const orc_plan *src, const int64_t *rounds, int64_t n)
+{
+    if (!src || n < 0 || (n > 0 && !rounds)) return NULL;
+    const int r = src->r, r1 = src->r + 1;
+    for (int64_t i = 0; i < n; i++)
+        if (rounds[i] < 0 || rounds[i] >= src->n_round) return NULL;
+    orc_plan *p = (orc_plan *)calloc(1, sizeof(orc_plan));
+    if (!p) return NULL;
+    *p = *src;
+    p->n_round = n;
+    const size_t nb = (size_t)src->n_batch, nr = (size_t)(n > 0 ? n : 1);
+    p->batch_job = (int *)malloc(sizeof(int) * nb);
+    p->batch_file0 = (int *)malloc(sizeof(int) * nb);
+    p->batch_label = (int *)malloc(sizeof(int) * nb * (size_t)r);
+    p->round_member = (int *)malloc(sizeof(int) * nr * (size_t)r1);
+    p->round_batch = (int *)malloc(sizeof(int) * nr * (size_t)r1);
+    if (!p->batch_job || !p->batch_file0 || !p->batch_label || !p->round_member || !p->round_batch) {
+        orc_plan_free(p);
+        return NULL;
+    }
+    memcpy(p->batch_job, src->batch_job, sizeof(int) * nb);
+    memcpy(p->batch_file0, src->batch_file0, sizeof(int) * nb);
+    memcpy(p->batch_label, src->batch_label, sizeof(int) * nb * (size_t)r);
+    for (int64_t i = 0; i < n; i++) {
+        memcpy(p->round_member + i * r1, src->round_member + rounds[i] * r1, sizeof(int) * (size_t)r1);
+        memcpy(p->round_batch + i * r1, src->round_batch + rounds[i] * r1, sizeof(int) * (size_t)r1);
+    }
+    return p;
+}
+
 /* Sec. IV-B says the packet is split evenly into r segments and silently
  * assumes r | W.  Reading used here: if 4r | W the split is exact; otherwise
  * ell = ceil(W/r) rounded up to a multiple of 4 elements, segment rho covers

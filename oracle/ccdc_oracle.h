@@ -81,6 +81,8 @@ int64_t orc_binom(int n, int k);
  */
 orc_plan *orc_plan_build(int K, int r, int Q, int N, int schedule, const int *batch_order, int order_sets);
 void orc_plan_free(orc_plan *p);
+/* Same batches, only the listed rounds (for sampling a large schedule); NULL on bad index. */
+orc_plan *orc_plan_select_rounds(const orc_plan *src, const int64_t *rounds, int64_t n);
 
 /* Segment length ell for a packet of W elements cut into r segments. */
 int64_t orc_segment_len(int64_t W, int r);

@@ -58,6 +58,8 @@ def _load():
     lib.orc_binom.argtypes = [C.c_int, C.c_int]
     lib.orc_plan_build.restype = P
     lib.orc_plan_build.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_int), C.c_int]
+    lib.orc_plan_select_rounds.restype = P
+    lib.orc_plan_select_rounds.argtypes = [P, C.POINTER(C.c_int64), C.c_int64]
     lib.orc_plan_free.restype = None
     lib.orc_plan_free.argtypes = [P]
     lib.orc_segment_len.restype = C.c_int64
@@ -136,6 +138,16 @@ def build_plan(K, r, Q, N, schedule="single", batch_order=None):
     ptr = lib.orc_plan_build(K, r, Q, N, sched, order, sets)
     if not ptr:
         raise ValueError(f"invalid parameters K={K} r={r} Q={Q} N={N} schedule={schedule}")
+    return OraclePlan(ptr)
+
+
+def select_rounds(plan, rounds):
+    """Plan with the same batches and only the listed rounds (sampling a large schedule)."""
+    rounds = [int(u) for u in rounds]
+    arr = (C.c_int64 * max(1, len(rounds)))(*rounds)
+    ptr = _load().orc_plan_select_rounds(plan._ptr, arr, len(rounds))
+    if not ptr:
+        raise ValueError("bad round index")
     return OraclePlan(ptr)
 
 

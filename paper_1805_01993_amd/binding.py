@@ -1,0 +1,234 @@
+"""ctypes binding of libccdc.so: same names as the C entry points, argument
+marshalling only.  PyTorch supplies device memory and streams; every step of
+the path runs in the library's kernels.  There is no CPU fallback: a missing
+or unloadable library raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from fractions import Fraction
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libccdc.so")
+
+OK, EINVAL, ENOMEM, EHIP, ESIZE, ESTATE = 0, -1, -2, -3, -4, -5
+F32_SUM, U32_XOR = 0, 1
+MODES = {"f32": F32_SUM, "u32": U32_XOR}
+
+# enum ccdc_query
+(Q_K, Q_R, Q_Q, Q_N, Q_J, Q_C, Q_M, Q_NBATCH, Q_NROUND, Q_T, Q_MODE, Q_W, Q_SEG_LEN,
+ Q_SCHEDULED_ELEMS, Q_CLOSED_FORM_NUM, Q_CLOSED_FORM_DEN, Q_V_ELEMS, Q_VBAR_ELEMS, Q_X_ELEMS,
+ Q_D_ELEMS, Q_PHI_ELEMS, Q_WORKSPACE_BYTES) = range(22)
+(Q_PACKET_LEN, Q_BATCH_JOB, Q_BATCH_FILE0, Q_BATCH_LABEL, Q_ROUND_MEMBER, Q_ROUND_BATCH) = range(64, 70)
+
+EXPORTS = [
+    "ccdc_plan", "ccdc_plan_jobs", "ccdc_plan_destroy", "ccdc_plan_bind", "ccdc_plan_upload",
+    "ccdc_plan_query", "ccdc_strerror", "ccdc_combine", "ccdc_encode", "ccdc_decode", "ccdc_reduce",
+    "ccdc_shuffle_fused",
+]
+
+
+class CcdcError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__(f"{where}: {strerror(status)} ({status})")
+
+
+_lib = None
+
+
+def load_library():
+    """Load libccdc.so (built in-tree by build.py).  Raises if it is not there."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            f"{LIB_PATH} is missing: build it first (python -m paper_1805_01993_amd.build "
+            "or __graft_entry__.build()); there is no fallback path")
+    try:
+        import torch  # noqa: F401  (loads the HIP runtime the process will share)
+    except Exception:
+        pass
+    lib = C.CDLL(LIB_PATH)
+    vp, i64 = C.c_void_p, C.c_int64
+    lib.ccdc_plan.restype = C.c_int
+    lib.ccdc_plan.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, C.POINTER(vp)]
+    lib.ccdc_plan_jobs.restype = C.c_int
+    lib.ccdc_plan_jobs.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, C.POINTER(vp)]
+    lib.ccdc_plan_destroy.restype = None
+    lib.ccdc_plan_destroy.argtypes = [vp]
+    lib.ccdc_plan_bind.restype = C.c_int
+    lib.ccdc_plan_bind.argtypes = [vp, i64, C.c_int]
+    lib.ccdc_plan_upload.restype = C.c_int
+    lib.ccdc_plan_upload.argtypes = [vp]
+    lib.ccdc_plan_query.restype = C.c_int
+    lib.ccdc_plan_query.argtypes = [vp, C.c_int, vp, C.c_size_t]
+    lib.ccdc_strerror.restype = C.c_char_p
+    lib.ccdc_strerror.argtypes = [C.c_int]
+    for name, nptr in (("ccdc_combine", 2), ("ccdc_encode", 2), ("ccdc_decode", 3), ("ccdc_reduce", 3),
+                       ("ccdc_shuffle_fused", 3)):
+        fn = getattr(lib, name)
+        fn.restype = C.c_int
+        fn.argtypes = [vp] + [vp] * nptr + [vp]
+    _lib = lib
+    return lib
+
+
+def strerror(status):
+    return load_library().ccdc_strerror(status).decode()
+
+
+def _check(status, where):
+    if status != OK:
+        raise CcdcError(status, where)
+
+
+def _dev_ptr(t, name):
+    """Device address of a contiguous CUDA/HIP torch tensor."""
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError(f"{name}: need a contiguous device tensor")
+    if t.element_size() != 4:
+        raise ValueError(f"{name}: need 4-byte elements, got {t.dtype}")
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream_ptr(stream):
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+class Plan:
+    """Owns one ccdc_plan_t.  Methods mirror the C entry points."""
+
+    def __init__(self, K, r, Q, N, jobs=False):
+        lib = load_library()
+        h = C.c_void_p()
+        fn = lib.ccdc_plan_jobs if jobs else lib.ccdc_plan
+        _check(fn(K, r, Q, N, C.byref(h)), "ccdc_plan_jobs" if jobs else "ccdc_plan")
+        self._h = h
+        self._lib = lib
+
+    def close(self):
+        if getattr(self, "_h", None):
+            self._lib.ccdc_plan_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # ---- plan construction
+    def bind(self, T, mode):
+        _check(self._lib.ccdc_plan_bind(self._h, int(T), MODES.get(mode, mode)), "ccdc_plan_bind")
+        return self
+
+    def upload(self):
+        _check(self._lib.ccdc_plan_upload(self._h), "ccdc_plan_upload")
+        return self
+
+    # ---- introspection
+    def query(self, what):
+        v = C.c_int64()
+        _check(self._lib.ccdc_plan_query(self._h, what, C.byref(v), 8), f"ccdc_plan_query({what})")
+        return int(v.value)
+
+    def query_table(self, what, shape, dtype):
+        out = np.empty(shape, dtype=dtype)
+        _check(self._lib.ccdc_plan_query(self._h, what, out.ctypes.data_as(C.c_void_p), out.nbytes),
+               f"ccdc_plan_query({what})")
+        return out
+
+    @property
+    def K(self): return self.query(Q_K)
+    @property
+    def r(self): return self.query(Q_R)
+    @property
+    def Q(self): return self.query(Q_Q)
+    @property
+    def N(self): return self.query(Q_N)
+    @property
+    def J(self): return self.query(Q_J)
+    @property
+    def c(self): return self.query(Q_C)
+    @property
+    def m(self): return self.query(Q_M)
+    @property
+    def n_batch(self): return self.query(Q_NBATCH)
+    @property
+    def n_round(self): return self.query(Q_NROUND)
+    @property
+    def T(self): return self.query(Q_T)
+    @property
+    def W(self): return self.query(Q_W)
+    @property
+    def seg_len(self): return self.query(Q_SEG_LEN)
+    @property
+    def scheduled_elems(self): return self.query(Q_SCHEDULED_ELEMS)
+    @property
+    def closed_form_elems(self):
+        return Fraction(self.query(Q_CLOSED_FORM_NUM), self.query(Q_CLOSED_FORM_DEN))
+    @property
+    def workspace_bytes(self): return self.query(Q_WORKSPACE_BYTES)
+
+    def tables(self):
+        nb, R, r = self.n_batch, self.n_round, self.r
+        return {
+            "batch_job": self.query_table(Q_BATCH_JOB, (nb,), np.int32),
+            "batch_file0": self.query_table(Q_BATCH_FILE0, (nb,), np.int32),
+            "batch_label": self.query_table(Q_BATCH_LABEL, (nb, r), np.int32),
+            "round_member": self.query_table(Q_ROUND_MEMBER, (R, r + 1), np.int32),
+            "round_batch": self.query_table(Q_ROUND_BATCH, (R, r + 1), np.int32),
+        }
+
+    def packet_len(self):
+        return self.query_table(Q_PACKET_LEN, (self.r + 1,), np.int64)
+
+    def shapes(self):
+        R, r1, W, ell = self.n_round, self.r + 1, self.W, self.seg_len
+        return {"V": (self.J, self.N, self.Q, self.T), "Vbar": (R, r1, W), "X": (R, r1, ell),
+                "D": (R, r1, W), "Phi": (self.J, self.Q, self.T)}
+
+    def _need(self, t, key, name):
+        want = int(np.prod(self.shapes()[key]))
+        if t.numel() != want:
+            raise ValueError(f"{name}: need {want} elements, got {t.numel()}")
+        return _dev_ptr(t, name)
+
+    # ---- stages (asynchronous on `stream`, default torch's current stream)
+    def combine(self, V, Vbar, stream=None):
+        _check(self._lib.ccdc_combine(self._h, self._need(V, "V", "V"), self._need(Vbar, "Vbar", "Vbar"),
+                                      _stream_ptr(stream)), "ccdc_combine")
+
+    def encode(self, Vbar, X, stream=None):
+        _check(self._lib.ccdc_encode(self._h, self._need(Vbar, "Vbar", "Vbar"), self._need(X, "X", "X"),
+                                     _stream_ptr(stream)), "ccdc_encode")
+
+    def decode(self, X, Vbar, D, stream=None):
+        _check(self._lib.ccdc_decode(self._h, self._need(X, "X", "X"), self._need(Vbar, "Vbar", "Vbar"),
+                                     self._need(D, "D", "D"), _stream_ptr(stream)), "ccdc_decode")
+
+    def reduce(self, V, D, Phi, stream=None):
+        _check(self._lib.ccdc_reduce(self._h, self._need(V, "V", "V"), self._need(D, "D", "D"),
+                                     self._need(Phi, "Phi", "Phi"), _stream_ptr(stream)), "ccdc_reduce")
+
+    def shuffle_fused(self, V, X, D, stream=None):
+        _check(self._lib.ccdc_shuffle_fused(self._h, self._need(V, "V", "V"), self._need(X, "X", "X"),
+                                            self._need(D, "D", "D"), _stream_ptr(stream)), "ccdc_shuffle_fused")
+
+
+def ccdc_plan(K, r, Q, N):
+    """Single-job placement and schedule (one batch per r-subset of the cluster)."""
+    return Plan(K, r, Q, N, jobs=False)
+
+
+def ccdc_plan_jobs(K, r, Q, N):
+    """The paper's J = C(K, r+1)-job placement and two-stage schedule."""
+    return Plan(K, r, Q, N, jobs=True)

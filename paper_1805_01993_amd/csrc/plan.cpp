@@ -1,0 +1,275 @@
+// Host side of the plan: file placement (Sec. IV-A), round schedule (Sec. IV-B),
+// segment split and the index tables the kernels consume.  Subsets are handled
+// through their lexicographic rank (combinatorial number system), no subset
+// table is ever materialised.
+#include "plan.hpp"
+
+#include <algorithm>
+#include <limits>
+#include <new>
+
+namespace ccdc {
+namespace {
+
+constexpr int64_t kMaxTable = 2147483647LL;          // int32 indexable
+constexpr int64_t kMaxElems = 1LL << 40;             // per buffer
+constexpr int64_t kMaxItems = 2147483647LL;          // work items of one launch
+
+// Pascal's triangle with saturation, C[n][k] for 0 <= k <= n <= nmax.
+struct Binom {
+    int nmax;
+    std::vector<int64_t> tab;
+    explicit Binom(int n) : nmax(n), tab((size_t)(n + 1) * (n + 1), 0) {
+        const int64_t cap = std::numeric_limits<int64_t>::max() / 2;
+        for (int i = 0; i <= n; i++) {
+            at(i, 0) = 1;
+            for (int k = 1; k <= i; k++) at(i, k) = std::min(cap, at(i - 1, k - 1) + (k <= i - 1 ? at(i - 1, k) : 0));
+        }
+    }
+    int64_t &at(int n, int k) { return tab[(size_t)n * (nmax + 1) + k]; }
+    int64_t operator()(int n, int k) const {
+        if (n < 0 || k < 0 || k > n) return 0;
+        return tab[(size_t)n * (nmax + 1) + k];
+    }
+};
+
+// Number of k-subsets of {0..n-1} that precede the ascending subset s in
+// lexicographic order.
+int64_t lex_rank(const Binom &C, int n, int k, const int *s)
+{
+    int64_t rank = 0;
+    int lo = 0;
+    for (int i = 0; i < k; i++) {
+        // subsets that agree on s[0..i-1] and have a smaller element at position i
+        for (int v = lo; v < s[i]; v++) rank += C(n - 1 - v, k - 1 - i);
+        lo = s[i] + 1;
+    }
+    return rank;
+}
+
+// Inverse of lex_rank.
+void lex_unrank(const Binom &C, int n, int k, int64_t rank, int *s)
+{
+    int v = 0;
+    for (int i = 0; i < k; i++) {
+        while (C(n - 1 - v, k - 1 - i) <= rank) {
+            rank -= C(n - 1 - v, k - 1 - i);
+            v++;
+        }
+        s[i] = v++;
+    }
+}
+
+}  // namespace
+
+int build_plan(int K, int r, int Q, int N, bool paper_jobs, ccdc_plan_t **out)
+{
+    if (!out) return CCDC_EINVAL;
+    *out = nullptr;
+    // Sec. III network model (K | Q, K <= N) and Theorem 1 (mu*K in 1..K-1)
+    if (K < 2 || r < 1 || r > K - 1 || Q < 1 || N < 1 || Q % K != 0 || K > N) return CCDC_EINVAL;
+    if (K > 4096) return CCDC_ESIZE;
+
+    const Binom C(K);
+    const int r1 = r + 1;
+    const int64_t nlabel = C(K, r), G = C(K, r1);
+    if (nlabel > kMaxTable || G > kMaxTable) return CCDC_ESIZE;
+    const int64_t per_job = paper_jobs ? r1 : nlabel;
+    if (N % per_job != 0) return CCDC_EINVAL;                 // Sec. IV-A: even batches
+    const int64_t nround = paper_jobs ? G * (K - r) : G;
+    const int64_t nbatch = paper_jobs ? G * r1 : nlabel;
+    if (nround * r1 > kMaxTable || nbatch * r > kMaxTable) return CCDC_ESIZE;
+
+    ccdc_plan_t *p = new (std::nothrow) ccdc_plan_t;
+    if (!p) return CCDC_ENOMEM;
+    try {
+        p->K = K; p->r = r; p->Q = Q; p->N = N;
+        p->c = Q / K;
+        p->m = (int)(N / per_job);
+        p->paper_jobs = paper_jobs;
+        p->J = paper_jobs ? (int)G : 1;
+        p->nbatch = nbatch;
+        p->nround = nround;
+        p->batch_job.resize((size_t)nbatch);
+        p->batch_file0.resize((size_t)nbatch);
+        p->batch_label.resize((size_t)nbatch * r);
+        p->round_member.resize((size_t)nround * r1);
+        p->round_batch.resize((size_t)nround * r1);
+
+        std::vector<int> S(r1 + 1), P(r1 + 1);
+        if (!paper_jobs) {
+            // One job over the whole cluster: batch p <-> p-th r-subset.
+            for (int64_t b = 0; b < nbatch; b++) {
+                lex_unrank(C, K, r, b, P.data());
+                p->batch_job[b] = 0;
+                p->batch_file0[b] = (int32_t)(b * p->m);
+                std::copy(P.begin(), P.begin() + r, p->batch_label.begin() + b * r);
+            }
+            // Round u <-> u-th (r+1)-subset; member b is served the batch whose
+            // label is the subset without s_b.
+            for (int64_t u = 0; u < nround; u++) {
+                lex_unrank(C, K, r1, u, S.data());
+                for (int b = 0; b < r1; b++) {
+                    p->round_member[u * r1 + b] = S[b];
+                    int w = 0;
+                    for (int i = 0; i < r1; i++)
+                        if (i != b) P[w++] = S[i];
+                    p->round_batch[u * r1 + b] = (int32_t)lex_rank(C, K, r, P.data());
+                }
+            }
+        } else {
+            // Job j lives on the j-th (r+1)-subset K_j.  Its r+1 batches are its
+            // r-subsets in lexicographic order: local batch q drops position r-q.
+            for (int64_t j = 0; j < G; j++) {
+                lex_unrank(C, K, r1, j, S.data());
+                for (int q = 0; q < r1; q++) {
+                    const int64_t bt = j * r1 + q;
+                    p->batch_job[bt] = (int32_t)j;
+                    p->batch_file0[bt] = q * p->m;
+                    int w = 0;
+                    for (int i = 0; i < r1; i++)
+                        if (i != r - q) p->batch_label[bt * r + w++] = S[i];
+                }
+            }
+            int64_t u = 0;
+            for (int64_t j = 0; j < G; j++) {
+                lex_unrank(C, K, r1, j, S.data());
+                // stage 1: job j inside K_j
+                for (int b = 0; b < r1; b++) {
+                    p->round_member[u * r1 + b] = S[b];
+                    p->round_batch[u * r1 + b] = (int32_t)(j * r1 + (r - b));
+                }
+                u++;
+                // stage 2: one round per outside node i.  Member s_b is served the
+                // batch labelled K_j \ {s_b} of the job living on K_j \ {s_b} + {i}.
+                int next_member = 0;
+                for (int i = 0; i < K; i++) {
+                    if (next_member < r1 && S[next_member] == i) { next_member++; continue; }
+                    for (int b = 0; b < r1; b++) {
+                        int w = 0, pos = -1;
+                        for (int t = 0; t < r1; t++) {
+                            if (t == b) continue;
+                            if (pos < 0 && S[t] > i) { pos = w; P[w++] = i; }
+                            P[w++] = S[t];
+                        }
+                        if (pos < 0) { pos = w; P[w++] = i; }
+                        const int64_t jb = lex_rank(C, K, r1, P.data());
+                        p->round_member[u * r1 + b] = S[b];
+                        p->round_batch[u * r1 + b] = (int32_t)(jb * r1 + (r - pos));
+                    }
+                    u++;
+                }
+            }
+        }
+    } catch (const std::bad_alloc &) {
+        delete p;
+        return CCDC_ENOMEM;
+    }
+    *out = p;
+    return CCDC_OK;
+}
+
+int bind_plan(ccdc_plan_t *p, int64_t T, int mode)
+{
+    if (!p || T < 1 || (mode != CCDC_F32_SUM && mode != CCDC_U32_XOR)) return CCDC_EINVAL;
+    const int r = p->r, r1 = r + 1;
+    if (T > kMaxElems / p->c) return CCDC_ESIZE;
+    const int64_t W = (int64_t)p->c * T;
+
+    // Split of a packet into r segments (Sec. IV-B): exact when 4r | W, else
+    // ceil(W/r) rounded up to a multiple of 4 elements with a short/empty tail.
+    int64_t ell;
+    if (W % (4 * (int64_t)r) == 0) {
+        ell = W / r;
+    } else {
+        ell = (W + r - 1) / r;
+        ell = (ell + 3) / 4 * 4;
+    }
+
+    // size limits of buffers and of one launch
+    const double v_elems = (double)p->J * p->N * p->Q * (double)T;
+    const double rows = (double)p->nround * r1;
+    if (v_elems > (double)kMaxElems || rows * (double)W > (double)kMaxElems) return CCDC_ESIZE;
+    const int vec = (T % 4 == 0) ? 4 : 1;
+    if (rows * (double)((W + vec - 1) / vec) > (double)kMaxItems) return CCDC_ESIZE;
+
+    try {
+        // true length of what sender a transmits: the longest segment it carries
+        std::vector<int64_t> plen(r1, 0);
+        int64_t per_round = 0;
+        for (int a = 0; a < r1; a++) {
+            for (int b = 0; b < r1; b++) {
+                if (b == a) continue;
+                const int64_t lo = label_rank(a, b) * ell;
+                const int64_t cnt = lo >= W ? 0 : std::min(ell, W - lo);
+                plen[a] = std::max(plen[a], cnt);
+            }
+            per_round += plen[a];
+        }
+
+        // where each round's r+1 packets are combined from
+        std::vector<int64_t> src((size_t)p->nround * r1);
+        for (int64_t i = 0; i < p->nround * r1; i++) {
+            const int32_t bt = p->round_batch[i];
+            const int64_t file = (int64_t)p->batch_job[bt] * p->N + p->batch_file0[bt];
+            src[i] = (file * p->Q + (int64_t)p->round_member[i] * p->c) * T;
+        }
+
+        // Row lists of the final reduction: for output block (job, node) first the
+        // files the node stores itself (batch order), then what it decoded (round order).
+        const int64_t nout = (int64_t)p->J * p->K;
+        std::vector<int64_t> cnt((size_t)nout + 1, 0);
+        for (int64_t bt = 0; bt < p->nbatch; bt++)
+            for (int s = 0; s < r; s++)
+                cnt[(int64_t)p->batch_job[bt] * p->K + p->batch_label[bt * r + s] + 1] += p->m;
+        for (int64_t i = 0; i < p->nround * r1; i++)
+            cnt[(int64_t)p->batch_job[p->round_batch[i]] * p->K + p->round_member[i] + 1] += 1;
+        for (int64_t o = 0; o < nout; o++) cnt[o + 1] += cnt[o];
+        std::vector<int64_t> rows_tab((size_t)cnt[nout]);
+        std::vector<int64_t> fill(cnt.begin(), cnt.end() - 1);
+        for (int64_t bt = 0; bt < p->nbatch; bt++)
+            for (int s = 0; s < r; s++) {
+                const int k = p->batch_label[bt * r + s];
+                const int64_t o = (int64_t)p->batch_job[bt] * p->K + k;
+                for (int f = 0; f < p->m; f++) {
+                    const int64_t file = (int64_t)p->batch_job[bt] * p->N + p->batch_file0[bt] + f;
+                    rows_tab[fill[o]++] = ((file * p->Q + (int64_t)k * p->c) * T) << 1;
+                }
+            }
+        for (int64_t i = 0; i < p->nround * r1; i++) {
+            const int64_t o = (int64_t)p->batch_job[p->round_batch[i]] * p->K + p->round_member[i];
+            rows_tab[fill[o]++] = ((i * W) << 1) | 1;
+        }
+        std::vector<int64_t> outs((size_t)nout);
+        int64_t min_rows = std::numeric_limits<int64_t>::max();
+        for (int64_t o = 0; o < nout; o++) {
+            outs[o] = ((o / p->K) * p->Q + (o % p->K) * (int64_t)p->c) * T;
+            min_rows = std::min(min_rows, cnt[o + 1] - cnt[o]);
+        }
+
+        // Few, long outputs (small T, many rounds) would leave the chip idle: cut
+        // each row list into red_split chunks summed by different workgroups and
+        // added up, in chunk order, by a second pass.
+        const int64_t items = nout * ((W + vec - 1) / vec);
+        int64_t split = 1;
+        if (items < (1 << 18)) split = std::min<int64_t>({(int64_t)256, std::max<int64_t>(1, min_rows), ((1 << 19) + items - 1) / items});
+        if (items * split > kMaxItems) return CCDC_ESIZE;
+
+        p->T = T; p->W = W; p->ell = ell; p->mode = mode;
+        p->packet_len.swap(plen);
+        p->scheduled = per_round * p->nround;
+        p->src_off.swap(src);
+        p->red_ptr.swap(cnt);
+        p->red_row.swap(rows_tab);
+        p->red_out.swap(outs);
+        p->nout = nout;
+        p->red_split = (int)split;
+        p->workspace_bytes = split > 1 ? (size_t)split * (size_t)p->J * p->Q * (size_t)T * 4 : 0;
+        p->bound = true;
+    } catch (const std::bad_alloc &) {
+        return CCDC_ENOMEM;
+    }
+    return CCDC_OK;
+}
+
+}  // namespace ccdc

@@ -1,0 +1,60 @@
+// Internal layout of a plan: host combinatorics, the bound segment schedule and
+// the handles of the device tables.  Not part of the public interface.
+#pragma once
+
+#include <cstddef>
+#include <cstdint>
+#include <vector>
+
+#include "ccdc.h"
+
+struct ccdc_plan_s {
+    // problem (Sec. III): per job
+    int K = 0, r = 0, Q = 0, N = 0;
+    int J = 1;            // jobs
+    int c = 0;            // Q / K functions per node
+    int m = 0;            // files per batch
+    bool paper_jobs = false;
+    int64_t nbatch = 0, nround = 0;
+
+    // placement (Sec. IV-A) and rounds (Sec. IV-B)
+    std::vector<int32_t> batch_job;     // [nbatch]
+    std::vector<int32_t> batch_file0;   // [nbatch]
+    std::vector<int32_t> batch_label;   // [nbatch][r]
+    std::vector<int32_t> round_member;  // [nround][r+1]
+    std::vector<int32_t> round_batch;   // [nround][r+1]
+
+    // fixed by ccdc_plan_bind
+    bool bound = false;
+    int64_t T = 0, W = 0, ell = 0;
+    int mode = 0;
+    std::vector<int64_t> packet_len;    // [r+1]
+    int64_t scheduled = 0;              // elements on the wire
+
+    // tables the kernels read (host copies)
+    std::vector<int64_t> src_off;       // [nround][r+1] element offset in V of the served
+                                        //   batch's first file, at the target's functions
+    std::vector<int64_t> red_ptr;       // [nout+1] row-list bounds of each (job, node) output
+    std::vector<int64_t> red_row;       // rows: (element offset << 1) | (1 = in D, 0 = in V)
+    std::vector<int64_t> red_out;       // [nout] element offset of the output block in Phi
+    int64_t nout = 0;                   // J * K output blocks of W elements
+    int red_split = 1;                  // the row list of an output is summed in this many chunks
+    size_t workspace_bytes = 0;
+
+    // device side, set by ccdc_plan_upload
+    bool uploaded = false;
+    int device = -1;
+    int64_t *d_src_off = nullptr, *d_red_ptr = nullptr, *d_red_row = nullptr, *d_red_out = nullptr;
+    void *d_workspace = nullptr;
+};
+
+namespace ccdc {
+
+// Host-side construction; both return a ccdc_status.
+int build_plan(int K, int r, int Q, int N, bool paper_jobs, ccdc_plan_t **out);
+int bind_plan(ccdc_plan_t *p, int64_t T, int mode);
+
+// Rank of sender a's label among the members other than b.
+inline int label_rank(int a, int b) { return a - (a > b ? 1 : 0); }
+
+}  // namespace ccdc

@@ -1,0 +1,272 @@
+"""Parity of the HIP path with the CPU oracle, element by element, through the
+C entry points.  Same seeded inputs on both sides; uint32/XOR must be bit-exact,
+fp32 must be within 1e-5 (max abs error over max abs reference, per artefact)
+of the fp64 oracle.  Needs a GPU."""
+import numpy as np
+import pytest
+
+import oracle as O
+from workloads import CONFIGS, generate_numpy, generate_torch
+
+pytestmark = pytest.mark.gpu
+
+F32_TOL = 1e-5
+
+
+@pytest.fixture(scope="module")
+def torch():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.fail("no GPU visible: the parity tests cannot run")
+    torch.cuda.set_device(0)
+    return torch
+
+
+@pytest.fixture(scope="module")
+def L(torch):
+    import paper_1805_01993_amd as lib
+    lib.load_library()          # fails loudly when the extension is not built
+    return lib
+
+
+def to_dev(torch, a):
+    if a.dtype == np.uint32:
+        a = a.view(np.int32)
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def to_host(t, mode):
+    a = t.cpu().numpy()
+    return a.view(np.uint32) if mode == "u32" else a
+
+
+def dev_empty(torch, shape, mode, fill=None):
+    dt = torch.float32 if mode == "f32" else torch.int32
+    t = torch.empty(shape, dtype=dt, device="cuda")
+    if fill is not None:
+        t.fill_(fill)
+    return t
+
+
+def assert_close(got, want, mode, name):
+    assert got.shape == want.shape, name
+    if mode == "u32":
+        bad = np.flatnonzero(got.ravel() != want.ravel())
+        assert bad.size == 0, f"{name}: {bad.size} words differ, first at {bad[:4]}"
+    else:
+        scale = float(np.abs(want).max())
+        err = float(np.abs(got.astype(np.float64) - want).max())
+        assert err <= F32_TOL * max(scale, 1e-300), f"{name}: err {err:.3e} scale {scale:.3e}"
+
+
+def run_case(torch, L, K, r, Q, N, T, mode, jobs=False, seed=1, sigma=1.0):
+    op = O.build_plan(K, r, Q, N, "paper" if jobs else "single")
+    Vh = generate_numpy(op.J, N, Q, T, seed, mode, sigma)
+    ref = O.run_all(op, T, Vh)
+    ref_phi = O.direct(op, T, Vh)
+
+    plan = L.Plan(K, r, Q, N, jobs=jobs).bind(T, mode).upload()
+    sh = plan.shapes()
+    V = to_dev(torch, Vh)
+    poison = float("nan") if mode == "f32" else -1
+    Vbar = dev_empty(torch, sh["Vbar"], mode, poison)
+    X = dev_empty(torch, sh["X"], mode, poison)
+    D = dev_empty(torch, sh["D"], mode, poison)
+    Phi = dev_empty(torch, sh["Phi"], mode, poison)
+    plan.combine(V, Vbar)
+    plan.encode(Vbar, X)
+    plan.decode(X, Vbar, D)
+    plan.reduce(V, D, Phi)
+    torch.cuda.synchronize()
+    got = {"Vbar": to_host(Vbar, mode), "X": to_host(X, mode), "D": to_host(D, mode), "Phi": to_host(Phi, mode)}
+    for name in ("Vbar", "X", "D", "Phi"):
+        assert_close(got[name], ref[name], mode, name)
+    assert_close(got["Phi"], ref_phi, mode, "Phi vs eq.(1)")
+
+    # fused combine+encode+decode: same artefacts, never materialising Vbar
+    X2 = dev_empty(torch, sh["X"], mode, poison)
+    D2 = dev_empty(torch, sh["D"], mode, poison)
+    plan.shuffle_fused(V, X2, D2)
+    torch.cuda.synchronize()
+    assert_close(to_host(X2, mode), ref["X"], mode, "fused X")
+    assert_close(to_host(D2, mode), ref["D"], mode, "fused D")
+    # same operation order as the separate stages: identical bits in both modes
+    assert torch.equal(X2.view(torch.int32), X.view(torch.int32))
+    assert torch.equal(D2.view(torch.int32), D.view(torch.int32))
+    Phi2 = dev_empty(torch, sh["Phi"], mode, poison)
+    plan.reduce(V, D2, Phi2)
+    torch.cuda.synchronize()
+    assert torch.equal(Phi2.view(torch.int32), Phi.view(torch.int32))
+    plan.close()
+    return got
+
+
+# ---------------------------------------------------------------- workloads
+
+@pytest.mark.parametrize("name,mode", [("cfg1_tiny", "f32"), ("cfg1_tiny", "u32"),
+                                       ("cfg2_k10", "f32"), ("cfg2_k10", "u32"),
+                                       ("cfg4_k16", "f32")])
+@pytest.mark.parametrize("seed", [1, 2])
+def test_small_workloads_full_compare(torch, L, name, mode, seed):
+    w = CONFIGS[name]
+    run_case(torch, L, w.K, w.r, w.Q, w.N, w.T, mode, seed=seed, sigma=w.sigma)
+
+
+# ------------------------------------------------------ shapes and edge cases
+
+EDGE = [
+    # K, r, Q, N, T, jobs      what it exercises
+    (3, 2, 3, 6, 1024, False),    # K = r+1: one round, the paper's own motivating example shape
+    (6, 1, 6, 12, 520, False),    # r = 1: uncoded unicast packets
+    (5, 4, 5, 10, 64, False),     # r = K-1 with 4r | W
+    (5, 3, 10, 20, 1000, False),  # c = 2, m = 2, r does not divide W (aligned split, short tail)
+    (4, 2, 4, 12, 7, False),      # T not a multiple of 4: scalar path, ragged tail
+    (4, 3, 4, 4, 10, False),      # tiny W: ell = 4, segments 4,4,2
+    (4, 3, 4, 4, 1, False),       # W = 1: all but the first segment empty
+    (6, 3, 12, 40, 333, False),   # scalar path over several tiles, c = 2, m = 2
+    (7, 5, 7, 21, 2052, False),   # r = 5
+    (10, 8, 10, 45, 36, False),   # r = 8: largest unrolled fused kernel
+    (11, 9, 11, 55, 40, False),   # r = 9: any-r fused fallback
+    (4, 2, 4, 6, 512, True),      # paper's 4-job running example shape
+    (5, 2, 10, 6, 258, True),     # J = 10 jobs, c = 2, scalar path
+    (6, 3, 6, 8, 1200, True),     # J = 15 jobs, m = 2
+]
+
+
+@pytest.mark.parametrize("K,r,Q,N,T,jobs", EDGE)
+@pytest.mark.parametrize("mode", ["u32", "f32"])
+def test_edge_shapes(torch, L, K, r, Q, N, T, jobs, mode):
+    run_case(torch, L, K, r, Q, N, T, mode, jobs=jobs, seed=K * 10 + r)
+
+
+def test_unaligned_pointers_take_the_scalar_path(torch, L):
+    """Buffers that are only 4-byte aligned still work; others are refused."""
+    K, r, Q, N, T, mode = 5, 2, 5, 10, 64, "u32"
+    op = O.build_plan(K, r, Q, N)
+    Vh = generate_numpy(1, N, Q, T, 3, mode)
+    ref = O.run_all(op, T, Vh)
+    plan = L.ccdc_plan(K, r, Q, N).bind(T, mode).upload()
+    sh = plan.shapes()
+
+    def shifted(shape):
+        n = int(np.prod(shape))
+        return torch.zeros(n + 1, dtype=torch.int32, device="cuda")[1:]
+
+    V = shifted(sh["V"])
+    V.copy_(to_dev(torch, Vh).reshape(-1))
+    X, D, Phi = shifted(sh["X"]), shifted(sh["D"]), shifted(sh["Phi"])
+    assert V.data_ptr() % 16 == 4
+    plan.shuffle_fused(V, X, D)
+    plan.reduce(V, D, Phi)
+    torch.cuda.synchronize()
+    assert_close(to_host(X, mode).reshape(sh["X"]), ref["X"], mode, "X")
+    assert_close(to_host(D, mode).reshape(sh["D"]), ref["D"], mode, "D")
+    assert_close(to_host(Phi, mode).reshape(sh["Phi"]), ref["Phi"], mode, "Phi")
+    import ctypes as C
+    lib = L.load_library()
+    assert lib.ccdc_encode(plan._h, C.c_void_p(D.data_ptr() + 1), C.c_void_p(X.data_ptr()), None) == L.binding.EINVAL
+    assert lib.ccdc_encode(plan._h, None, C.c_void_p(X.data_ptr()), None) == L.binding.EINVAL
+    plan.close()
+
+
+def test_results_are_deterministic_and_on_the_given_stream(torch, L):
+    w = CONFIGS["cfg2_k10"]
+    plan = L.ccdc_plan(w.K, w.r, w.Q, w.N).bind(w.T, "f32").upload()
+    sh = plan.shapes()
+    V = generate_torch(1, w.N, w.Q, w.T, 5, "f32", device="cuda")
+    outs = []
+    side = torch.cuda.Stream()
+    for stream in (None, side, None):
+        X = dev_empty(torch, sh["X"], "f32", float("nan"))
+        D = dev_empty(torch, sh["D"], "f32", float("nan"))
+        Phi = dev_empty(torch, sh["Phi"], "f32", float("nan"))
+        if stream is not None:
+            stream.wait_stream(torch.cuda.current_stream())
+        plan.shuffle_fused(V, X, D, stream=stream)
+        plan.reduce(V, D, Phi, stream=stream)
+        if stream is not None:
+            stream.synchronize()
+        torch.cuda.synchronize()
+        outs.append((X, D, Phi))
+    for X, D, Phi in outs[1:]:
+        assert torch.equal(X, outs[0][0]) and torch.equal(D, outs[0][1]) and torch.equal(Phi, outs[0][2])
+    plan.close()
+
+
+def test_rebinding_a_plan(torch, L):
+    plan = L.ccdc_plan(4, 2, 4, 12)
+    for T, mode in ((256, "f32"), (100, "u32"), (256, "u32")):
+        plan.bind(T, mode)
+        with pytest.raises(L.CcdcError):          # binding drops the device tables
+            plan.combine(torch.zeros(12 * 4 * T, dtype=torch.int32, device="cuda"),
+                         torch.zeros(plan.query(L.binding.Q_VBAR_ELEMS), dtype=torch.int32, device="cuda"))
+        plan.upload()
+        op = O.build_plan(4, 2, 4, 12)
+        Vh = generate_numpy(1, 12, 4, T, 9, mode)
+        V = to_dev(torch, Vh)
+        sh = plan.shapes()
+        X, D, Phi = (dev_empty(torch, sh[k], mode) for k in ("X", "D", "Phi"))
+        plan.shuffle_fused(V, X, D)
+        plan.reduce(V, D, Phi)
+        torch.cuda.synchronize()
+        assert_close(to_host(Phi, mode), O.direct(op, T, Vh), mode, "Phi")
+    plan.close()
+
+
+# --------------------------------------------- full-size workloads, sampled
+
+def full_size_case(torch, L, name, mode, n_rounds=48, seed=1):
+    """Inputs are generated on the device and copied back, so both sides see
+    the same bits.  The oracle runs the stages on a sample of rounds; the final
+    result is compared in full with the plain sum of eq. (1)."""
+    w = CONFIGS[name]
+    plan = L.ccdc_plan(w.K, w.r, w.Q, w.N).bind(w.T, mode).upload()
+    sh = plan.shapes()
+    V = generate_torch(1, w.N, w.Q, w.T, seed, mode, sigma=w.sigma, device="cuda")
+    poison = float("nan") if mode == "f32" else -1
+    X = dev_empty(torch, sh["X"], mode, poison)
+    D = dev_empty(torch, sh["D"], mode, poison)
+    Phi = dev_empty(torch, sh["Phi"], mode, poison)
+    plan.shuffle_fused(V, X, D)
+    plan.reduce(V, D, Phi)
+    torch.cuda.synchronize()
+    Vh = to_host(V, mode)
+    if mode == "f32":
+        want_phi = Vh.sum(axis=1, dtype=np.float64)
+    else:
+        want_phi = np.bitwise_xor.reduce(Vh, axis=1)
+    assert_close(to_host(Phi, mode), want_phi, mode, "Phi vs eq.(1)")
+
+    op = O.build_plan(w.K, w.r, w.Q, w.N)
+    rng = np.random.default_rng(seed)
+    rounds = sorted(set([0, op.n_round - 1] + rng.integers(0, op.n_round, n_rounds).tolist()))
+    sub = O.select_rounds(op, rounds)
+    vb = O.combine(sub, w.T, Vh)
+    xr = O.encode(sub, w.T, vb)
+    dr = O.decode(sub, w.T, xr, vb)
+    idx = torch.tensor(rounds, device="cuda")
+    assert_close(to_host(X[idx], mode), xr, mode, "X (sampled rounds)")
+    assert_close(to_host(D[idx], mode), dr, mode, "D (sampled rounds)")
+    # the separate stages on the same inputs give the same bits as the fused pass
+    Vbar = dev_empty(torch, sh["Vbar"], mode, poison)
+    X1 = dev_empty(torch, sh["X"], mode, poison)
+    plan.combine(V, Vbar)
+    plan.encode(Vbar, X1)
+    torch.cuda.synchronize()
+    assert torch.equal(X1.view(torch.int32), X.view(torch.int32))
+    del X1
+    D1 = dev_empty(torch, sh["D"], mode, poison)
+    plan.decode(X, Vbar, D1)
+    torch.cuda.synchronize()
+    assert torch.equal(D1.view(torch.int32), D.view(torch.int32))
+    assert_close(to_host(Vbar[idx], mode), vb, mode, "Vbar (sampled rounds)")
+    plan.close()
+
+
+@pytest.mark.parametrize("mode", ["f32", "u32"])
+def test_full_size_many_node_workload(torch, L, mode):
+    full_size_case(torch, L, "cfg5_k24", mode)
+
+
+def test_full_size_gradient_workload(torch, L):
+    full_size_case(torch, L, "cfg3_gradient", "f32", n_rounds=6)

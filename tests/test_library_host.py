@@ -1,0 +1,148 @@
+"""Host-side checks of libccdc.so that need no GPU: the library loads, exports
+every declared entry point, its plan tables equal the oracle's (the two share
+no code, only the numbering conventions), and its error paths answer with
+status codes.  No kernel is launched here."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle as O
+from paper_1805_01993_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(B.LIB_PATH):
+        from paper_1805_01993_amd.build import build_library
+        build_library()
+    return B.load_library()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "ccdc.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ccdc_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_functions()
+    assert len(names) >= 12
+    for name in names:
+        assert hasattr(lib, name), name
+    assert sorted(B.EXPORTS) == names        # the binding covers the whole header
+
+
+def test_library_does_not_link_the_oracle():
+    import subprocess
+    needed = subprocess.run(["readelf", "-d", B.LIB_PATH], capture_output=True, text=True).stdout
+    assert "oracle" not in needed
+    syms = subprocess.run(["nm", "-D", B.LIB_PATH], capture_output=True, text=True).stdout
+    assert "orc_" not in syms
+
+
+SWEEP = [(K, r, c, m) for K in range(2, 8) for r in range(1, K) for c in (1, 2) for m in (1, 2)]
+
+
+@pytest.mark.parametrize("jobs", [False, True])
+def test_plan_tables_equal_the_oracles(lib, jobs):
+    from math import comb
+    n = 0
+    for (K, r, c, m) in SWEEP:
+        nb = (r + 1) if jobs else comb(K, r)
+        while m * nb < K:
+            m += 1
+        Q, N = c * K, m * nb
+        p = B.Plan(K, r, Q, N, jobs=jobs)
+        o = O.build_plan(K, r, Q, N, "paper" if jobs else "single")
+        assert (p.J, p.c, p.m, p.n_batch, p.n_round) == (o.J, o.c, o.m, o.n_batch, o.n_round)
+        for name, tab in p.tables().items():
+            assert np.array_equal(tab, getattr(o, name)), (K, r, c, m, name)
+        for T in (1, 3, 4, 8, 10, 12, 40):
+            p.bind(T, "u32")
+            W = c * T
+            assert p.W == W and p.T == T
+            assert p.seg_len == O.segment_len(W, r)
+            assert p.scheduled_elems == O.scheduled_elems(o, T)
+            assert p.closed_form_elems == O.closed_form_elems(o, T)
+            assert p.packet_len().tolist() == [O.packet_len(W, r, a) for a in range(r + 1)]
+            sh, osh = p.shapes(), o.shapes(T)
+            assert all(tuple(sh[k]) == tuple(osh[k]) for k in osh)
+        p.close()
+        n += 1
+    assert n == len(SWEEP)
+
+
+def test_workload_plans(lib):
+    from workloads import CONFIGS
+    for w in CONFIGS.values():
+        p = B.ccdc_plan(w.K, w.r, w.Q, w.N).bind(w.T, w.modes[0])
+        o = O.build_plan(w.K, w.r, w.Q, w.N)
+        assert p.n_round == w.G and p.m == w.m
+        assert np.array_equal(p.tables()["round_batch"], o.round_batch)
+        assert p.scheduled_elems == O.scheduled_elems(o, w.T)
+        assert p.query(B.Q_V_ELEMS) == w.v_elems
+
+
+@pytest.mark.parametrize("args", [
+    (1, 1, 1, 4), (4, 0, 4, 12), (4, 4, 4, 12), (4, 2, 6, 12), (4, 2, 4, 3), (4, 2, 4, 13), (4, 2, 0, 12),
+])
+def test_invalid_parameters(lib, args):
+    h = C.c_void_p()
+    assert lib.ccdc_plan(*args, C.byref(h)) == B.EINVAL
+    assert not h.value
+    assert lib.ccdc_plan(4, 2, 4, 12, None) == B.EINVAL
+
+
+def test_too_many_subsets_is_a_size_error(lib):
+    h = C.c_void_p()
+    assert lib.ccdc_plan(64, 31, 64, 64, C.byref(h)) in (B.ESIZE, B.EINVAL)
+    assert lib.ccdc_plan(40, 19, 40, 40, C.byref(h)) in (B.ESIZE, B.EINVAL)
+    assert not h.value
+
+
+def test_state_and_argument_errors(lib):
+    p = B.ccdc_plan(4, 2, 4, 12)
+    v = C.c_int64()
+    assert lib.ccdc_plan_query(p._h, B.Q_K, C.byref(v), 8) == B.OK and v.value == 4
+    assert lib.ccdc_plan_query(p._h, B.Q_W, C.byref(v), 8) == B.ESTATE          # not bound yet
+    assert lib.ccdc_plan_query(p._h, 9999, C.byref(v), 8) == B.EINVAL
+    assert lib.ccdc_plan_query(p._h, B.Q_K, C.byref(v), 4) == B.EINVAL          # buffer too small
+    assert lib.ccdc_plan_query(p._h, B.Q_K, None, 8) == B.EINVAL
+    assert lib.ccdc_plan_query(None, B.Q_K, C.byref(v), 8) == B.EINVAL
+    small = (C.c_int32 * 2)()
+    assert lib.ccdc_plan_query(p._h, B.Q_ROUND_MEMBER, small, 8) == B.EINVAL
+    assert lib.ccdc_plan_upload(p._h) == B.ESTATE                                # not bound yet
+    assert lib.ccdc_plan_bind(p._h, 0, B.F32_SUM) == B.EINVAL
+    assert lib.ccdc_plan_bind(p._h, 16, 7) == B.EINVAL
+    assert lib.ccdc_plan_bind(None, 16, 0) == B.EINVAL
+    assert lib.ccdc_plan_bind(p._h, 1 << 41, B.F32_SUM) == B.ESIZE               # buffers past 2^40 elements
+    assert lib.ccdc_plan_bind(p._h, 1 << 33, B.F32_SUM) == B.ESIZE               # launch past 2^31-1 items
+    assert lib.ccdc_plan_bind(p._h, 16, B.F32_SUM) == B.OK
+    # stage calls on a plan that was never uploaded: refused, nothing launched
+    for fn, nptr in ((lib.ccdc_combine, 2), (lib.ccdc_encode, 2), (lib.ccdc_decode, 3), (lib.ccdc_reduce, 3),
+                     (lib.ccdc_shuffle_fused, 3)):
+        assert fn(p._h, *([C.c_void_p(256)] * nptr), None) == B.ESTATE
+        assert fn(None, *([C.c_void_p(256)] * nptr), None) == B.EINVAL
+    lib.ccdc_plan_destroy(None)                                                  # allowed
+    assert B.strerror(B.ESIZE) and B.strerror(-99) == "unknown status"
+
+
+def test_binding_refuses_to_run_without_the_library(monkeypatch, tmp_path):
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "libccdc.so"))
+    with pytest.raises(FileNotFoundError):
+        B.ccdc_plan(4, 2, 4, 12)
+
+
+def test_product_path_never_imports_the_oracle():
+    pkg = os.path.join(ROOT, "paper_1805_01993_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".cpp", ".hpp", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.lower().replace("no cpu fallback", ""), f
