@@ -1,0 +1,154 @@
+#!/usr/bin/env python3
+"""Throughput of the whole shuffle path (combine, encode, decode, reduce) on one MI355X.
+
+A step is one pass of the path over one batch of synthetic intermediate values
+that are already resident in HBM.  Prints ONE JSON line: logical GB/s of
+intermediate values (Q*N*T*4 bytes per step), the HBM roofline figure of the
+dominant kernel measured with events on its stream, and the CPU oracle timed
+on a bounded sample of the same workload as a reported baseline.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
+METRIC = "GB/s of intermediate values through combine+encode+decode; % of HBM peak"
+
+
+def algorithmic_bytes_shuffle(w, ell):
+    """Bytes one fused combine+encode+decode launch must move: every needed
+    element of V once, every coded packet and every decoded packet once."""
+    rounds, r1, W = w.G, w.r + 1, w.W
+    reads = rounds * r1 * w.m * W
+    writes = rounds * r1 * (ell + W)
+    return 4 * (reads + writes)
+
+
+def cpu_baseline(w, mode, T_sample):
+    """The oracle as it stands, single thread, on the same K, r, Q, N with a
+    shorter value length so the run stays bounded."""
+    import numpy as np
+
+    import oracle as O
+    from workloads import generate_numpy
+
+    op = O.build_plan(w.K, w.r, w.Q, w.N)
+    rng = np.random.default_rng(1)
+    if mode == "f32":
+        V = (w.sigma * rng.standard_normal((1, w.N, w.Q, T_sample), dtype=np.float32)).astype(np.float32)
+    else:
+        V = generate_numpy(1, w.N, w.Q, T_sample, 1, "u32")
+    t0 = time.perf_counter()
+    O.run_all(op, T_sample, V)
+    dt = time.perf_counter() - t0
+    return {"value": round(V.nbytes / dt / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": f"same K,r,Q,N with T={T_sample} ({V.nbytes / 1e6:.0f} MB of intermediate values), "
+                      f"all four stages, {dt:.1f} s",
+            "host_cpus": os.cpu_count()}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="cfg3_gradient")
+    ap.add_argument("--mode", default=None, help="f32 or u32 (default: the workload's first mode)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-T", type=int, default=0)
+    args = ap.parse_args()
+
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this path runs on one GPU only (all K nodes are emulated on it); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_1805_01993_amd as L
+    from workloads import CONFIGS, generate_torch
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    L.load_library()
+
+    w = CONFIGS[args.workload]
+    mode = args.mode or w.modes[0]
+    plan = L.ccdc_plan(w.K, w.r, w.Q, w.N).bind(w.T, mode).upload()
+    sh = plan.shapes()
+    dt = torch.float32 if mode == "f32" else torch.int32
+    V = generate_torch(1, w.N, w.Q, w.T, 1, mode, sigma=w.sigma, device="cuda")
+    X = torch.empty(sh["X"], dtype=dt, device="cuda")
+    D = torch.empty(sh["D"], dtype=dt, device="cuda")
+    Phi = torch.empty(sh["Phi"], dtype=dt, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    def step(events=None):
+        if events is not None:
+            events[0].record(stream)
+        plan.shuffle_fused(V, X, D, stream=stream)
+        if events is not None:
+            events[1].record(stream)
+        plan.reduce(V, D, Phi, stream=stream)
+        if events is not None:
+            events[2].record(stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(evs[i])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    ms_per_step = 1e3 * elapsed / args.steps
+    shuffle_ms = sum(e[0].elapsed_time(e[1]) for e in evs) / args.steps
+    reduce_ms = sum(e[1].elapsed_time(e[2]) for e in evs) / args.steps
+    v_bytes = w.v_bytes
+    value = v_bytes / (ms_per_step * 1e-3) / 1e9
+
+    alg = algorithmic_bytes_shuffle(w, plan.seg_len)
+    achieved = alg / (shuffle_ms * 1e-3) / 1e9
+    out = {
+        "metric": METRIC,
+        "value": round(value, 2),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": mode,
+        "data": "synthetic",
+        "config": {"workload": f"{w.name}: K={w.K} r={w.r} Q={w.Q} N={w.N} T={w.T} {mode}, single job, "
+                               f"{v_bytes / 1e9:.3f} GB of intermediate values per step",
+                   "path": "ccdc_shuffle_fused + ccdc_reduce"},
+        "pct_hbm_peak_logical": round(100 * value / HBM_PEAK_GBPS, 2),
+        "kernel_ms": {"shuffle_fused": round(shuffle_ms, 4), "reduce": round(reduce_ms, 4)},
+        "roofline": {"bound": "hbm", "kernel": "k_shuffle_fused", "achieved": round(achieved, 1),
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                     "algorithmic_bytes_per_launch": alg, "traffic": None},
+    }
+    if not args.no_cpu_baseline:
+        T_sample = args.cpu_sample_T or max(4, min(w.T, (1_000_000_000 // (4 * w.Q * w.N)) // 4 * 4))
+        out["cpu_baseline"] = cpu_baseline(w, mode, T_sample)
+    plan.close()
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()
