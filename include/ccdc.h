@@ -155,6 +155,18 @@ int ccdc_reduce(const ccdc_plan_t *plan, const void *V, const void *D, void *Phi
  * three separate calls (bit-exact in XOR mode; same operation order in fp32). */
 int ccdc_shuffle_fused(const ccdc_plan_t *plan, const void *V, void *X, void *D, void *stream);
 
+/* The whole path in one pass for single-job plans (ccdc_plan): combine, encode,
+ * decode and reduce; every element of V is read once, X and Phi are written,
+ * neither Vbar nor D is materialised.  Each coded pack is decoded for each
+ * receiver as in ccdc_decode (coded pack minus the receiver's side information)
+ * and added to that receiver's output, together with the files it stores itself.
+ * X equals ccdc_encode's bit for bit; Phi is bit-exact in XOR mode and, in fp32,
+ * a fixed summation order different from ccdc_reduce's.  Uses the plan's
+ * workspace.  CCDC_ESIZE for plans of ccdc_plan_jobs, for r > 5 and for
+ * K*r > 256 (the per-lane outputs of all nodes must fit in 64 KB of LDS):
+ * use ccdc_shuffle_fused + ccdc_reduce there. */
+int ccdc_pipeline_fused(const ccdc_plan_t *plan, const void *V, void *X, void *Phi, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

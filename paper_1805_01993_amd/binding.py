@@ -27,7 +27,7 @@ MODES = {"f32": F32_SUM, "u32": U32_XOR}
 EXPORTS = [
     "ccdc_plan", "ccdc_plan_jobs", "ccdc_plan_destroy", "ccdc_plan_bind", "ccdc_plan_upload",
     "ccdc_plan_query", "ccdc_strerror", "ccdc_combine", "ccdc_encode", "ccdc_decode", "ccdc_reduce",
-    "ccdc_shuffle_fused",
+    "ccdc_shuffle_fused", "ccdc_pipeline_fused",
 ]
 
 
@@ -70,7 +70,7 @@ def load_library():
     lib.ccdc_strerror.restype = C.c_char_p
     lib.ccdc_strerror.argtypes = [C.c_int]
     for name, nptr in (("ccdc_combine", 2), ("ccdc_encode", 2), ("ccdc_decode", 3), ("ccdc_reduce", 3),
-                       ("ccdc_shuffle_fused", 3)):
+                       ("ccdc_shuffle_fused", 3), ("ccdc_pipeline_fused", 3)):
         fn = getattr(lib, name)
         fn.restype = C.c_int
         fn.argtypes = [vp] + [vp] * nptr + [vp]
@@ -222,6 +222,11 @@ class Plan:
     def shuffle_fused(self, V, X, D, stream=None):
         _check(self._lib.ccdc_shuffle_fused(self._h, self._need(V, "V", "V"), self._need(X, "X", "X"),
                                             self._need(D, "D", "D"), _stream_ptr(stream)), "ccdc_shuffle_fused")
+
+    def pipeline_fused(self, V, X, Phi, stream=None):
+        _check(self._lib.ccdc_pipeline_fused(self._h, self._need(V, "V", "V"), self._need(X, "X", "X"),
+                                             self._need(Phi, "Phi", "Phi"), _stream_ptr(stream)),
+               "ccdc_pipeline_fused")
 
 
 def ccdc_plan(K, r, Q, N):

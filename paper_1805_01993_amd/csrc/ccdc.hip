@@ -212,6 +212,108 @@ __global__ __launch_bounds__(kBlock) void k_shuffle_fused(const typename A::elem
     }
 }
 
+// ------------------------------------------------- whole path in one pass
+// combine + encode + decode + reduce for a single-job plan.  A workgroup is one
+// wavefront; lane = in-segment pack x; the workgroup walks a chunk of rounds.
+// For a round it reads the r packs of each of the r+1 packets that sit at
+// x (every needed element of V once), forms each sender's coded pack (written
+// to X), decodes it for each receiver exactly as k_decode does, and adds the
+// decoded pack to the receiver's running output.  Those running outputs (K nodes
+// x r segments per lane) live in LDS, one private slot per lane, so there are no
+// atomics and no barriers and the summation order is fixed.  The files a node
+// stores itself are added from V the same way.  With more than one chunk the
+// per-chunk outputs go to the workspace and k_reduce_final adds them in order.
+template <class A, int VEC, int R1>
+__global__ __launch_bounds__(ccdc::kPipeLanes) void k_pipeline(
+    const typename A::elem *__restrict__ V, typename A::elem *__restrict__ X, typename A::elem *__restrict__ out,
+    const int64_t *__restrict__ src_off, const int32_t *__restrict__ member, const int64_t *__restrict__ loc_row,
+    int K, uint32_t Lv, uint32_t Wv, int m, int64_t file_stride, uint32_t R, uint32_t tiles, uint32_t chunks,
+    uint32_t n_loc, uint32_t loc_rows, int64_t chunk_stride)
+{
+    using E = typename A::elem;
+    using O = Ops<A, VEC>;
+    using P = typename O::P;
+    constexpr int r = R1 - 1;
+    constexpr int LANES = ccdc::kPipeLanes;
+    extern __shared__ __align__(16) unsigned char smem[];
+    P *acc = reinterpret_cast<P *>(smem) + threadIdx.x;      // slot i of this lane: acc[i * LANES]
+
+    const uint32_t tile = blockIdx.x % tiles, chunk = blockIdx.x / tiles;
+    const uint32_t x = tile * LANES + threadIdx.x;
+    if (x >= Lv) return;
+
+    bool valid[r];                    // does segment rho reach position x (short / empty tail)
+#pragma unroll
+    for (int rho = 0; rho < r; rho++) valid[rho] = rho * Lv + x < Wv;
+
+    for (int i = 0; i < K * r; i++) acc[i * LANES] = O::zero();
+
+    const uint32_t u0 = (uint32_t)((uint64_t)R * chunk / chunks);
+    const uint32_t u1 = (uint32_t)((uint64_t)R * (chunk + 1) / chunks);
+    for (uint32_t u = u0; u < u1; u++) {
+        const int64_t *src = src_off + (size_t)u * R1;
+        const int32_t *mem = member + (size_t)u * R1;
+        P w[R1][r];                   // w[b][rho]: pack x of segment rho of Vbar[u][b]
+#pragma unroll
+        for (int b = 0; b < R1; b++) {
+            const E *s = V + src[b] + (int64_t)x * VEC;
+#pragma unroll
+            for (int rho = 0; rho < r; rho++) {
+                if (valid[rho]) {
+                    const E *q = s + (int64_t)rho * Lv * VEC;
+                    P t = *reinterpret_cast<const P *>(q);
+                    for (int f = 1; f < m; f++) t = O::add(t, *reinterpret_cast<const P *>(q + f * file_stride));
+                    w[b][rho] = t;
+                } else {
+                    w[b][rho] = O::zero();
+                }
+            }
+        }
+#pragma unroll
+        for (int a = 0; a < R1; a++) {
+            P coded = O::zero();
+#pragma unroll
+            for (int b = 0; b < R1; b++)
+                if (b != a) coded = O::add(coded, w[b][a - (a > b ? 1 : 0)]);
+            reinterpret_cast<P *>(X)[((size_t)u * R1 + a) * Lv + x] = coded;
+#pragma unroll
+            for (int b = 0; b < R1; b++) {
+                if (b == a) continue;
+                const int rho = a - (a > b ? 1 : 0);
+                if (!valid[rho]) continue;
+                P d = coded;
+#pragma unroll
+                for (int b2 = 0; b2 < R1; b2++)
+                    if (b2 != a && b2 != b) d = O::sub(d, w[b2][a - (a > b2 ? 1 : 0)]);
+                P *slot = acc + (mem[b] * r + rho) * LANES;
+                *slot = O::add(*slot, d);
+            }
+        }
+    }
+
+    // the files each node stores itself
+    const uint32_t i0 = (uint32_t)((uint64_t)n_loc * chunk / chunks);
+    const uint32_t i1 = (uint32_t)((uint64_t)n_loc * (chunk + 1) / chunks);
+    for (uint32_t i = i0; i < i1; i++) {
+        const uint32_t k = i / loc_rows;
+        const E *row = V + loc_row[i] + (int64_t)x * VEC;
+#pragma unroll
+        for (int rho = 0; rho < r; rho++) {
+            if (!valid[rho]) continue;
+            P *slot = acc + (k * r + rho) * LANES;
+            *slot = O::add(*slot, *reinterpret_cast<const P *>(row + (int64_t)rho * Lv * VEC));
+        }
+    }
+
+    E *dst = out + (int64_t)chunk * chunk_stride + (int64_t)x * VEC;
+    const int64_t W = (int64_t)Wv * VEC;
+    for (int k = 0; k < K; k++) {
+#pragma unroll
+        for (int rho = 0; rho < r; rho++)
+            if (valid[rho]) *reinterpret_cast<P *>(dst + k * W + (int64_t)rho * Lv * VEC) = acc[(k * r + rho) * LANES];
+    }
+}
+
 // ------------------------------------------------------------------- reduce
 // Sec. IV-B final reduction as a gather-sum of rows: output block o (one node's
 // c functions of one job) is the sum of a list of W-long rows, some in V (files
@@ -299,7 +401,8 @@ int launched()
 void release_device(ccdc_plan_t *p)
 {
     if (!p) return;
-    if (p->uploaded || p->d_src_off || p->d_red_ptr || p->d_red_row || p->d_red_out || p->d_workspace) {
+    if (p->uploaded || p->d_src_off || p->d_red_ptr || p->d_red_row || p->d_red_out || p->d_loc_row || p->d_member ||
+        p->d_workspace) {
         int cur = -1;
         const bool sw = hipGetDevice(&cur) == hipSuccess && p->device >= 0 && cur != p->device &&
                         hipSetDevice(p->device) == hipSuccess;
@@ -307,10 +410,13 @@ void release_device(ccdc_plan_t *p)
         (void)hipFree(p->d_red_ptr);
         (void)hipFree(p->d_red_row);
         (void)hipFree(p->d_red_out);
+        (void)hipFree(p->d_loc_row);
+        (void)hipFree(p->d_member);
         (void)hipFree(p->d_workspace);
         if (sw) (void)hipSetDevice(cur);
     }
-    p->d_src_off = p->d_red_ptr = p->d_red_row = p->d_red_out = nullptr;
+    p->d_src_off = p->d_red_ptr = p->d_red_row = p->d_red_out = p->d_loc_row = nullptr;
+    p->d_member = nullptr;
     p->d_workspace = nullptr;
     p->uploaded = false;
     p->device = -1;
@@ -412,6 +518,46 @@ int run_reduce(const ccdc_plan_t *p, const void *V, const void *D, void *Phi, hi
     return launched();
 }
 
+template <class A, int VEC, int R1>
+void launch_pipeline(const ccdc_plan_t *p, const void *V, void *X, void *out, int chunks, hipStream_t st)
+{
+    using E = typename A::elem;
+    const uint32_t Wv = (uint32_t)(p->W / VEC), Lv = (uint32_t)(p->ell / VEC);
+    const uint32_t tiles = cdiv(Lv, ccdc::kPipeLanes);
+    const size_t lds = (size_t)p->K * p->r * ccdc::kPipeLanes * VEC * sizeof(E);
+    k_pipeline<A, VEC, R1><<<tiles * (uint32_t)chunks, ccdc::kPipeLanes, lds, st>>>(
+        (const E *)V, (E *)X, (E *)out, p->d_src_off, p->d_member, p->d_loc_row, p->K, Lv, Wv, p->m,
+        (int64_t)p->Q * p->T, (uint32_t)p->nround, tiles, (uint32_t)chunks, (uint32_t)(p->K * p->pipe_local_rows),
+        (uint32_t)p->pipe_local_rows, (int64_t)p->K * p->W);
+}
+
+template <class A, int VEC>
+int run_pipeline(const ccdc_plan_t *p, const void *V, void *X, void *Phi, bool wide_final, hipStream_t st)
+{
+    using E = typename A::elem;
+    const int chunks = ccdc::pipeline_chunks(p, VEC);
+    void *out = chunks > 1 ? p->d_workspace : Phi;
+    switch (p->r + 1) {
+    case 2: launch_pipeline<A, VEC, 2>(p, V, X, out, chunks, st); break;
+    case 3: launch_pipeline<A, VEC, 3>(p, V, X, out, chunks, st); break;
+    case 4: launch_pipeline<A, VEC, 4>(p, V, X, out, chunks, st); break;
+    case 5: launch_pipeline<A, VEC, 5>(p, V, X, out, chunks, st); break;
+    case 6: launch_pipeline<A, VEC, 6>(p, V, X, out, chunks, st); break;
+    default: return CCDC_ESIZE;
+    }
+    int rc = launched();
+    if (rc != CCDC_OK || chunks == 1) return rc;
+    const int64_t n = (int64_t)p->K * p->W;
+    if (wide_final) {
+        k_reduce_final<A, 4><<<cdiv(n / 4, kBlock), kBlock, 0, st>>>((const E *)p->d_workspace, (E *)Phi, chunks, n / 4,
+                                                                      (uint32_t)(n / 4));
+    } else {
+        k_reduce_final<A, 1><<<cdiv(n, kBlock), kBlock, 0, st>>>((const E *)p->d_workspace, (E *)Phi, chunks, n,
+                                                                  (uint32_t)n);
+    }
+    return launched();
+}
+
 // Dispatch on (mode, vec): F(algebra tag, vec tag).
 #define CCDC_DISPATCH(p, vec, CALL)                                   \
     do {                                                              \
@@ -467,6 +613,8 @@ int ccdc_plan_upload(ccdc_plan_t *plan)
     if (rc == CCDC_OK) rc = to_device(plan->red_ptr, &plan->d_red_ptr);
     if (rc == CCDC_OK) rc = to_device(plan->red_row, &plan->d_red_row);
     if (rc == CCDC_OK) rc = to_device(plan->red_out, &plan->d_red_out);
+    if (rc == CCDC_OK) rc = to_device(plan->loc_row, &plan->d_loc_row);
+    if (rc == CCDC_OK) rc = to_device(plan->round_member, &plan->d_member);
     if (rc == CCDC_OK && plan->workspace_bytes > 0 &&
         hipMalloc(&plan->d_workspace, plan->workspace_bytes) != hipSuccess) {
         plan->d_workspace = nullptr;
@@ -598,6 +746,27 @@ int ccdc_shuffle_fused(const ccdc_plan_t *plan, const void *V, void *X, void *D,
     if ((rc = pick_vec(plan, &vec, V, (const void *)X, (const void *)D)) != CCDC_OK) return rc;
     hipStream_t st = (hipStream_t)stream;
     CCDC_DISPATCH(plan, vec, (run_shuffle<A, VEC>(plan, V, X, D, st)));
+}
+
+int ccdc_pipeline_fused(const ccdc_plan_t *plan, const void *V, void *X, void *Phi, void *stream)
+{
+    int rc = ready(plan), vec4 = 1;
+    if (rc != CCDC_OK) return rc;
+    if (!plan->pipe_ok) return CCDC_ESIZE;
+    if ((rc = pick_vec(plan, &vec4, V, (const void *)X, (const void *)Phi)) != CCDC_OK) return rc;
+    // widest pack allowed by the plan's LDS budget and by the pointers
+    int vec = plan->pipe_vec;
+    while (vec > 1 && !(aligned(V, 4 * vec) && aligned(X, 4 * vec) && aligned(Phi, 4 * vec))) vec /= 2;
+    const bool wide_final = vec4 == 4;
+    hipStream_t st = (hipStream_t)stream;
+    if (plan->mode == CCDC_F32_SUM) {
+        if (vec == 4) return run_pipeline<SumF32, 4>(plan, V, X, Phi, wide_final, st);
+        if (vec == 2) return run_pipeline<SumF32, 2>(plan, V, X, Phi, wide_final, st);
+        return run_pipeline<SumF32, 1>(plan, V, X, Phi, wide_final, st);
+    }
+    if (vec == 4) return run_pipeline<XorU32, 4>(plan, V, X, Phi, wide_final, st);
+    if (vec == 2) return run_pipeline<XorU32, 2>(plan, V, X, Phi, wide_final, st);
+    return run_pipeline<XorU32, 1>(plan, V, X, Phi, wide_final, st);
 }
 
 }  // extern "C"

@@ -255,7 +255,41 @@ int bind_plan(ccdc_plan_t *p, int64_t T, int mode)
         if (items < (1 << 18)) split = std::min<int64_t>({(int64_t)256, std::max<int64_t>(1, min_rows), ((1 << 19) + items - 1) / items});
         if (items * split > kMaxItems) return CCDC_ESIZE;
 
+        // One-pass pipeline: single job, unrolled r, accumulators of K nodes x r
+        // segments per lane must fit in LDS.  The widest pack that still leaves
+        // several wavefronts per compute unit is preferred.
+        bool pipe_ok = !p->paper_jobs && r1 <= kPipeMaxR1 &&
+                       (int64_t)p->K * r * 4 * kPipeLanes <= kPipeMaxLds;
+        int pipe_vec = 1;
+        int64_t pipe_cap = 1, local_rows = 0;
+        std::vector<int64_t> loc;
+        if (pipe_ok) {
+            if (T % 4 == 0 && (int64_t)p->K * r * 16 * kPipeLanes <= kPipeGoodLds) pipe_vec = 4;
+            else if (T % 2 == 0 && (int64_t)p->K * r * 8 * kPipeLanes <= kPipeGoodLds) pipe_vec = 2;
+            // chunk partials are written and read once more: keep them under ~1/4 of |V|
+            const double v = (double)p->N * p->Q * (double)T, kw = (double)p->K * (double)W;
+            pipe_cap = std::max<int64_t>(1, std::min<int64_t>({(int64_t)1024, p->nround, (int64_t)(0.125 * v / kw)}));
+            // rows of V each node adds from its own files: the V entries of its
+            // reduce list (the same count for every node of a single job)
+            for (int64_t i = cnt[0]; i < cnt[1]; i++) local_rows += !(rows_tab[i] & 1);
+            loc.resize((size_t)p->K * local_rows);
+            for (int k = 0; k < p->K; k++) {
+                int64_t w = 0;
+                for (int64_t i = cnt[k]; i < cnt[k + 1]; i++)
+                    if (!(rows_tab[i] & 1)) {
+                        if (w < local_rows) loc[(size_t)k * local_rows + w] = rows_tab[i] >> 1;
+                        w++;
+                    }
+                if (w != local_rows) pipe_ok = false;
+            }
+        }
+
         p->T = T; p->W = W; p->ell = ell; p->mode = mode;
+        p->pipe_ok = pipe_ok;
+        p->pipe_vec = pipe_vec;
+        p->pipe_max_chunks = (int)pipe_cap;
+        p->pipe_local_rows = pipe_ok ? local_rows : 0;
+        p->loc_row.swap(loc);
         p->packet_len.swap(plen);
         p->scheduled = per_round * p->nround;
         p->src_off.swap(src);
@@ -265,11 +299,22 @@ int bind_plan(ccdc_plan_t *p, int64_t T, int mode)
         p->nout = nout;
         p->red_split = (int)split;
         p->workspace_bytes = split > 1 ? (size_t)split * (size_t)p->J * p->Q * (size_t)T * 4 : 0;
+        if (pipe_ok && pipe_cap > 1)
+            p->workspace_bytes = std::max(p->workspace_bytes, (size_t)pipe_cap * (size_t)p->K * (size_t)W * 4);
         p->bound = true;
     } catch (const std::bad_alloc &) {
         return CCDC_ENOMEM;
     }
     return CCDC_OK;
+}
+
+int pipeline_chunks(const ccdc_plan_t *p, int vec)
+{
+    // enough workgroups to fill 256 compute units several times over, but never
+    // more chunks than the workspace was sized for
+    const int64_t tiles = ((p->ell + vec - 1) / vec + kPipeLanes - 1) / kPipeLanes;
+    const int64_t want = (2048 + tiles - 1) / tiles;
+    return (int)std::max<int64_t>(1, std::min<int64_t>(want, p->pipe_max_chunks));
 }
 
 }  // namespace ccdc

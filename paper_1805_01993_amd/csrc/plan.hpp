@@ -41,10 +41,20 @@ struct ccdc_plan_s {
     int red_split = 1;                  // the row list of an output is summed in this many chunks
     size_t workspace_bytes = 0;
 
+    // whole path in one pass (single-job plans): the partial outputs of all K
+    // nodes are accumulated in LDS, one private slot per (node, segment, lane)
+    bool pipe_ok = false;               // shape supported by ccdc_pipeline_fused
+    int pipe_vec = 1;                   // widest pack the LDS budget allows
+    int pipe_max_chunks = 1;            // upper bound on round chunks (sizes the workspace)
+    int64_t pipe_local_rows = 0;        // rows of V every node adds from its own files
+    std::vector<int64_t> loc_row;       // [K][pipe_local_rows] element offsets in V
+
     // device side, set by ccdc_plan_upload
     bool uploaded = false;
     int device = -1;
     int64_t *d_src_off = nullptr, *d_red_ptr = nullptr, *d_red_row = nullptr, *d_red_out = nullptr;
+    int64_t *d_loc_row = nullptr;
+    int32_t *d_member = nullptr;
     void *d_workspace = nullptr;
 };
 
@@ -53,6 +63,15 @@ namespace ccdc {
 // Host-side construction; both return a ccdc_status.
 int build_plan(int K, int r, int Q, int N, bool paper_jobs, ccdc_plan_t **out);
 int bind_plan(ccdc_plan_t *p, int64_t T, int mode);
+
+// Limits of the one-pass pipeline kernel.
+constexpr int kPipeLanes = 64;                 // one wavefront per workgroup
+constexpr int kPipeMaxLds = 64 * 1024;         // bytes of LDS one workgroup may take
+constexpr int kPipeGoodLds = 26 * 1024;        // keeps >= 6 wavefronts per compute unit
+constexpr int kPipeMaxR1 = 6;                  // r+1 the kernel is unrolled for
+
+// Number of round chunks the pipeline kernel uses for a given pack width.
+int pipeline_chunks(const ccdc_plan_t *p, int vec);
 
 // Rank of sender a's label among the members other than b.
 inline int label_rank(int a, int b) { return a - (a > b ? 1 : 0); }

@@ -97,6 +97,20 @@ def run_case(torch, L, K, r, Q, N, T, mode, jobs=False, seed=1, sigma=1.0):
     plan.reduce(V, D2, Phi2)
     torch.cuda.synchronize()
     assert torch.equal(Phi2.view(torch.int32), Phi.view(torch.int32))
+
+    # the whole path in one pass (single-job plans, r <= 5, K*r <= 256)
+    X3 = dev_empty(torch, sh["X"], mode, poison)
+    Phi3 = dev_empty(torch, sh["Phi"], mode, poison)
+    if not jobs and r <= 5 and K * r <= 256:
+        plan.pipeline_fused(V, X3, Phi3)
+        torch.cuda.synchronize()
+        assert torch.equal(X3.view(torch.int32), X.view(torch.int32))
+        assert_close(to_host(Phi3, mode), ref["Phi"], mode, "pipeline Phi")
+        assert_close(to_host(Phi3, mode), ref_phi, mode, "pipeline Phi vs eq.(1)")
+    else:
+        with pytest.raises(L.CcdcError) as err:
+            plan.pipeline_fused(V, X3, Phi3)
+        assert err.value.status == L.binding.ESIZE
     plan.close()
     return got
 
@@ -260,6 +274,14 @@ def full_size_case(torch, L, name, mode, n_rounds=48, seed=1):
     torch.cuda.synchronize()
     assert torch.equal(D1.view(torch.int32), D.view(torch.int32))
     assert_close(to_host(Vbar[idx], mode), vb, mode, "Vbar (sampled rounds)")
+    del Vbar, D1
+    # the one-pass pipeline in the launch configuration the benchmark times
+    X3 = dev_empty(torch, sh["X"], mode, poison)
+    Phi3 = dev_empty(torch, sh["Phi"], mode, poison)
+    plan.pipeline_fused(V, X3, Phi3)
+    torch.cuda.synchronize()
+    assert torch.equal(X3.view(torch.int32), X.view(torch.int32))
+    assert_close(to_host(Phi3, mode), want_phi, mode, "pipeline Phi vs eq.(1)")
     plan.close()
 
 
