@@ -4,63 +4,12 @@
 // work item moves one pack (16 bytes when T is a multiple of 4, else one
 // element) per operand, consecutive lanes touch consecutive packs of the same
 // row, and there is no reuse across work items, so no LDS tiling and no MFMA.
-#include <hip/hip_runtime.h>
-
-#include <cstdint>
 #include <new>
 
-#include "ccdc.h"
-#include "plan.hpp"
+#include "common.hpp"
 
 namespace {
-
-// ----------------------------------------------------------------- algebras
-struct SumF32 {
-    using elem = float;
-    static __device__ __forceinline__ elem zero() { return 0.0f; }
-    static __device__ __forceinline__ elem add(elem a, elem b) { return a + b; }
-    static __device__ __forceinline__ elem sub(elem a, elem b) { return a - b; }
-};
-struct XorU32 {
-    using elem = uint32_t;
-    static __device__ __forceinline__ elem zero() { return 0u; }
-    static __device__ __forceinline__ elem add(elem a, elem b) { return a ^ b; }
-    static __device__ __forceinline__ elem sub(elem a, elem b) { return a ^ b; }
-};
-
-// VEC consecutive elements moved by one load/store.
-template <class E, int VEC>
-struct alignas(sizeof(E) * VEC) Pack {
-    E v[VEC];
-};
-
-template <class A, int VEC>
-struct Ops {
-    using P = Pack<typename A::elem, VEC>;
-    static __device__ __forceinline__ P zero()
-    {
-        P z;
-#pragma unroll
-        for (int i = 0; i < VEC; i++) z.v[i] = A::zero();
-        return z;
-    }
-    static __device__ __forceinline__ P add(P a, P b)
-    {
-#pragma unroll
-        for (int i = 0; i < VEC; i++) a.v[i] = A::add(a.v[i], b.v[i]);
-        return a;
-    }
-    static __device__ __forceinline__ P sub(P a, P b)
-    {
-#pragma unroll
-        for (int i = 0; i < VEC; i++) a.v[i] = A::sub(a.v[i], b.v[i]);
-        return a;
-    }
-};
-
-constexpr int kBlock = 256;
-
-__device__ __forceinline__ int label_rank(int a, int b) { return a - (a > b ? 1 : 0); }
+using namespace ccdc;
 
 // ------------------------------------------------------------------ combine
 // Sec. IV-B pre-combining.  One work item = one pack of one packet Vbar[u][b]:
@@ -212,108 +161,6 @@ __global__ __launch_bounds__(kBlock) void k_shuffle_fused(const typename A::elem
     }
 }
 
-// ------------------------------------------------- whole path in one pass
-// combine + encode + decode + reduce for a single-job plan.  A workgroup is one
-// wavefront; lane = in-segment pack x; the workgroup walks a chunk of rounds.
-// For a round it reads the r packs of each of the r+1 packets that sit at
-// x (every needed element of V once), forms each sender's coded pack (written
-// to X), decodes it for each receiver exactly as k_decode does, and adds the
-// decoded pack to the receiver's running output.  Those running outputs (K nodes
-// x r segments per lane) live in LDS, one private slot per lane, so there are no
-// atomics and no barriers and the summation order is fixed.  The files a node
-// stores itself are added from V the same way.  With more than one chunk the
-// per-chunk outputs go to the workspace and k_reduce_final adds them in order.
-template <class A, int VEC, int R1>
-__global__ __launch_bounds__(ccdc::kPipeLanes) void k_pipeline(
-    const typename A::elem *__restrict__ V, typename A::elem *__restrict__ X, typename A::elem *__restrict__ out,
-    const int64_t *__restrict__ src_off, const int32_t *__restrict__ member, const int64_t *__restrict__ loc_row,
-    int K, uint32_t Lv, uint32_t Wv, int m, int64_t file_stride, uint32_t R, uint32_t tiles, uint32_t chunks,
-    uint32_t n_loc, uint32_t loc_rows, int64_t chunk_stride)
-{
-    using E = typename A::elem;
-    using O = Ops<A, VEC>;
-    using P = typename O::P;
-    constexpr int r = R1 - 1;
-    constexpr int LANES = ccdc::kPipeLanes;
-    extern __shared__ __align__(16) unsigned char smem[];
-    P *acc = reinterpret_cast<P *>(smem) + threadIdx.x;      // slot i of this lane: acc[i * LANES]
-
-    const uint32_t tile = blockIdx.x % tiles, chunk = blockIdx.x / tiles;
-    const uint32_t x = tile * LANES + threadIdx.x;
-    if (x >= Lv) return;
-
-    bool valid[r];                    // does segment rho reach position x (short / empty tail)
-#pragma unroll
-    for (int rho = 0; rho < r; rho++) valid[rho] = rho * Lv + x < Wv;
-
-    for (int i = 0; i < K * r; i++) acc[i * LANES] = O::zero();
-
-    const uint32_t u0 = (uint32_t)((uint64_t)R * chunk / chunks);
-    const uint32_t u1 = (uint32_t)((uint64_t)R * (chunk + 1) / chunks);
-    for (uint32_t u = u0; u < u1; u++) {
-        const int64_t *src = src_off + (size_t)u * R1;
-        const int32_t *mem = member + (size_t)u * R1;
-        P w[R1][r];                   // w[b][rho]: pack x of segment rho of Vbar[u][b]
-#pragma unroll
-        for (int b = 0; b < R1; b++) {
-            const E *s = V + src[b] + (int64_t)x * VEC;
-#pragma unroll
-            for (int rho = 0; rho < r; rho++) {
-                if (valid[rho]) {
-                    const E *q = s + (int64_t)rho * Lv * VEC;
-                    P t = *reinterpret_cast<const P *>(q);
-                    for (int f = 1; f < m; f++) t = O::add(t, *reinterpret_cast<const P *>(q + f * file_stride));
-                    w[b][rho] = t;
-                } else {
-                    w[b][rho] = O::zero();
-                }
-            }
-        }
-#pragma unroll
-        for (int a = 0; a < R1; a++) {
-            P coded = O::zero();
-#pragma unroll
-            for (int b = 0; b < R1; b++)
-                if (b != a) coded = O::add(coded, w[b][a - (a > b ? 1 : 0)]);
-            reinterpret_cast<P *>(X)[((size_t)u * R1 + a) * Lv + x] = coded;
-#pragma unroll
-            for (int b = 0; b < R1; b++) {
-                if (b == a) continue;
-                const int rho = a - (a > b ? 1 : 0);
-                if (!valid[rho]) continue;
-                P d = coded;
-#pragma unroll
-                for (int b2 = 0; b2 < R1; b2++)
-                    if (b2 != a && b2 != b) d = O::sub(d, w[b2][a - (a > b2 ? 1 : 0)]);
-                P *slot = acc + (mem[b] * r + rho) * LANES;
-                *slot = O::add(*slot, d);
-            }
-        }
-    }
-
-    // the files each node stores itself
-    const uint32_t i0 = (uint32_t)((uint64_t)n_loc * chunk / chunks);
-    const uint32_t i1 = (uint32_t)((uint64_t)n_loc * (chunk + 1) / chunks);
-    for (uint32_t i = i0; i < i1; i++) {
-        const uint32_t k = i / loc_rows;
-        const E *row = V + loc_row[i] + (int64_t)x * VEC;
-#pragma unroll
-        for (int rho = 0; rho < r; rho++) {
-            if (!valid[rho]) continue;
-            P *slot = acc + (k * r + rho) * LANES;
-            *slot = O::add(*slot, *reinterpret_cast<const P *>(row + (int64_t)rho * Lv * VEC));
-        }
-    }
-
-    E *dst = out + (int64_t)chunk * chunk_stride + (int64_t)x * VEC;
-    const int64_t W = (int64_t)Wv * VEC;
-    for (int k = 0; k < K; k++) {
-#pragma unroll
-        for (int rho = 0; rho < r; rho++)
-            if (valid[rho]) *reinterpret_cast<P *>(dst + k * W + (int64_t)rho * Lv * VEC) = acc[(k * r + rho) * LANES];
-    }
-}
-
 // ------------------------------------------------------------------- reduce
 // Sec. IV-B final reduction as a gather-sum of rows: output block o (one node's
 // c functions of one job) is the sum of a list of W-long rows, some in V (files
@@ -347,55 +194,6 @@ __global__ __launch_bounds__(kBlock) void k_reduce_rows(const typename A::elem *
         acc = O::add(acc, reinterpret_cast<const P *>(base + (row >> 1))[e]);
     }
     reinterpret_cast<P *>(out + (int64_t)s * chunk_stride + red_out[o])[e] = acc;
-}
-
-template <class A, int VEC>
-__global__ __launch_bounds__(kBlock) void k_reduce_final(const typename A::elem *__restrict__ part,
-                                                         typename A::elem *__restrict__ Phi, int split,
-                                                         int64_t chunk_packs, uint32_t items)
-{
-    using O = Ops<A, VEC>;
-    using P = typename O::P;
-    const uint32_t idx = blockIdx.x * kBlock + threadIdx.x;
-    if (idx >= items) return;
-    const P *src = reinterpret_cast<const P *>(part) + idx;
-    P acc = src[0];
-    for (int s = 1; s < split; s++) acc = O::add(acc, src[(int64_t)s * chunk_packs]);
-    reinterpret_cast<P *>(Phi)[idx] = acc;
-}
-
-// ------------------------------------------------------------ host helpers
-inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
-inline uint32_t cdiv(uint64_t a, uint64_t b) { return (uint32_t)((a + b - 1) / b); }
-
-int ready(const ccdc_plan_t *p)
-{
-    if (!p) return CCDC_EINVAL;
-    if (!p->bound || !p->uploaded) return CCDC_ESTATE;
-    int dev = -1;
-    if (hipGetDevice(&dev) != hipSuccess) return CCDC_EHIP;
-    if (dev != p->device) return CCDC_ESTATE;
-    return CCDC_OK;
-}
-
-// Pack width for this call: 4 when the value length and every pointer allow it.
-template <class... Ptr>
-int pick_vec(const ccdc_plan_t *p, int *vec, Ptr... ptrs)
-{
-    const void *list[] = {ptrs...};
-    bool a16 = true;
-    for (const void *q : list) {
-        if (!q) return CCDC_EINVAL;
-        if (!aligned(q, 4)) return CCDC_EINVAL;
-        a16 = a16 && aligned(q, 16);
-    }
-    *vec = (p->T % 4 == 0 && a16) ? 4 : 1;
-    return CCDC_OK;
-}
-
-int launched()
-{
-    return hipGetLastError() == hipSuccess ? CCDC_OK : CCDC_EHIP;
 }
 
 void release_device(ccdc_plan_t *p)
@@ -515,46 +313,6 @@ int run_reduce(const ccdc_plan_t *p, const void *V, const void *D, void *Phi, hi
     const uint64_t items = (uint64_t)chunk_stride / VEC;
     k_reduce_final<A, VEC><<<cdiv(items, kBlock), kBlock, 0, st>>>((const E *)p->d_workspace, (E *)Phi, split,
                                                                     chunk_stride / VEC, (uint32_t)items);
-    return launched();
-}
-
-template <class A, int VEC, int R1>
-void launch_pipeline(const ccdc_plan_t *p, const void *V, void *X, void *out, int chunks, hipStream_t st)
-{
-    using E = typename A::elem;
-    const uint32_t Wv = (uint32_t)(p->W / VEC), Lv = (uint32_t)(p->ell / VEC);
-    const uint32_t tiles = cdiv(Lv, ccdc::kPipeLanes);
-    const size_t lds = (size_t)p->K * p->r * ccdc::kPipeLanes * VEC * sizeof(E);
-    k_pipeline<A, VEC, R1><<<tiles * (uint32_t)chunks, ccdc::kPipeLanes, lds, st>>>(
-        (const E *)V, (E *)X, (E *)out, p->d_src_off, p->d_member, p->d_loc_row, p->K, Lv, Wv, p->m,
-        (int64_t)p->Q * p->T, (uint32_t)p->nround, tiles, (uint32_t)chunks, (uint32_t)(p->K * p->pipe_local_rows),
-        (uint32_t)p->pipe_local_rows, (int64_t)p->K * p->W);
-}
-
-template <class A, int VEC>
-int run_pipeline(const ccdc_plan_t *p, const void *V, void *X, void *Phi, bool wide_final, hipStream_t st)
-{
-    using E = typename A::elem;
-    const int chunks = ccdc::pipeline_chunks(p, VEC);
-    void *out = chunks > 1 ? p->d_workspace : Phi;
-    switch (p->r + 1) {
-    case 2: launch_pipeline<A, VEC, 2>(p, V, X, out, chunks, st); break;
-    case 3: launch_pipeline<A, VEC, 3>(p, V, X, out, chunks, st); break;
-    case 4: launch_pipeline<A, VEC, 4>(p, V, X, out, chunks, st); break;
-    case 5: launch_pipeline<A, VEC, 5>(p, V, X, out, chunks, st); break;
-    case 6: launch_pipeline<A, VEC, 6>(p, V, X, out, chunks, st); break;
-    default: return CCDC_ESIZE;
-    }
-    int rc = launched();
-    if (rc != CCDC_OK || chunks == 1) return rc;
-    const int64_t n = (int64_t)p->K * p->W;
-    if (wide_final) {
-        k_reduce_final<A, 4><<<cdiv(n / 4, kBlock), kBlock, 0, st>>>((const E *)p->d_workspace, (E *)Phi, chunks, n / 4,
-                                                                      (uint32_t)(n / 4));
-    } else {
-        k_reduce_final<A, 1><<<cdiv(n, kBlock), kBlock, 0, st>>>((const E *)p->d_workspace, (E *)Phi, chunks, n,
-                                                                  (uint32_t)n);
-    }
     return launched();
 }
 
@@ -746,27 +504,6 @@ int ccdc_shuffle_fused(const ccdc_plan_t *plan, const void *V, void *X, void *D,
     if ((rc = pick_vec(plan, &vec, V, (const void *)X, (const void *)D)) != CCDC_OK) return rc;
     hipStream_t st = (hipStream_t)stream;
     CCDC_DISPATCH(plan, vec, (run_shuffle<A, VEC>(plan, V, X, D, st)));
-}
-
-int ccdc_pipeline_fused(const ccdc_plan_t *plan, const void *V, void *X, void *Phi, void *stream)
-{
-    int rc = ready(plan), vec4 = 1;
-    if (rc != CCDC_OK) return rc;
-    if (!plan->pipe_ok) return CCDC_ESIZE;
-    if ((rc = pick_vec(plan, &vec4, V, (const void *)X, (const void *)Phi)) != CCDC_OK) return rc;
-    // widest pack allowed by the plan's LDS budget and by the pointers
-    int vec = plan->pipe_vec;
-    while (vec > 1 && !(aligned(V, 4 * vec) && aligned(X, 4 * vec) && aligned(Phi, 4 * vec))) vec /= 2;
-    const bool wide_final = vec4 == 4;
-    hipStream_t st = (hipStream_t)stream;
-    if (plan->mode == CCDC_F32_SUM) {
-        if (vec == 4) return run_pipeline<SumF32, 4>(plan, V, X, Phi, wide_final, st);
-        if (vec == 2) return run_pipeline<SumF32, 2>(plan, V, X, Phi, wide_final, st);
-        return run_pipeline<SumF32, 1>(plan, V, X, Phi, wide_final, st);
-    }
-    if (vec == 4) return run_pipeline<XorU32, 4>(plan, V, X, Phi, wide_final, st);
-    if (vec == 2) return run_pipeline<XorU32, 2>(plan, V, X, Phi, wide_final, st);
-    return run_pipeline<XorU32, 1>(plan, V, X, Phi, wide_final, st);
 }
 
 }  // extern "C"

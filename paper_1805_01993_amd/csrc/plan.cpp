@@ -308,13 +308,4 @@ int bind_plan(ccdc_plan_t *p, int64_t T, int mode)
     return CCDC_OK;
 }
 
-int pipeline_chunks(const ccdc_plan_t *p, int vec)
-{
-    // enough workgroups to fill 256 compute units several times over, but never
-    // more chunks than the workspace was sized for
-    const int64_t tiles = ((p->ell + vec - 1) / vec + kPipeLanes - 1) / kPipeLanes;
-    const int64_t want = (2048 + tiles - 1) / tiles;
-    return (int)std::max<int64_t>(1, std::min<int64_t>(want, p->pipe_max_chunks));
-}
-
 }  // namespace ccdc

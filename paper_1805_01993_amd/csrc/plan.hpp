@@ -70,9 +70,6 @@ constexpr int kPipeMaxLds = 64 * 1024;         // bytes of LDS one workgroup may
 constexpr int kPipeGoodLds = 26 * 1024;        // keeps >= 6 wavefronts per compute unit
 constexpr int kPipeMaxR1 = 6;                  // r+1 the kernel is unrolled for
 
-// Number of round chunks the pipeline kernel uses for a given pack width.
-int pipeline_chunks(const ccdc_plan_t *p, int vec);
-
 // Rank of sender a's label among the members other than b.
 inline int label_rank(int a, int b) { return a - (a > b ? 1 : 0); }
 
