@@ -311,8 +311,9 @@ int run_reduce(const ccdc_plan_t *p, const void *V, const void *D, void *Phi, hi
     int rc = launched();
     if (rc != CCDC_OK || split == 1) return rc;
     const uint64_t items = (uint64_t)chunk_stride / VEC;
-    k_reduce_final<A, VEC><<<cdiv(items, kBlock), kBlock, 0, st>>>((const E *)p->d_workspace, (E *)Phi, split,
-                                                                    chunk_stride / VEC, (uint32_t)items);
+    const int G = reduce_final_groups((int64_t)items, split);
+    k_reduce_final<A, VEC><<<cdiv(items, kBlock / G), kBlock, 0, st>>>((const E *)p->d_workspace, (E *)Phi, split,
+                                                                        chunk_stride / VEC, (uint32_t)items, G);
     return launched();
 }
 

@@ -52,25 +52,53 @@ struct Ops {
         for (int i = 0; i < VEC; i++) a.v[i] = A::sub(a.v[i], b.v[i]);
         return a;
     }
+    static __device__ __forceinline__ P select(bool c, P a, P b)
+    {
+#pragma unroll
+        for (int i = 0; i < VEC; i++) a.v[i] = c ? a.v[i] : b.v[i];
+        return a;
+    }
 };
 
 constexpr int kBlock = 256;
 
 __device__ __forceinline__ int label_rank(int a, int b) { return a - (a > b ? 1 : 0); }
 
+// Phi = sum over chunks of the per-chunk outputs part[split][chunk_packs].
+// A workgroup owns kBlock/G consecutive packs; its G thread groups each add
+// every G-th chunk (g, g+G, ...), then the G group sums are added in group
+// order.  The order is fixed by (split, G), so results repeat run to run.
 template <class A, int VEC>
 __global__ __launch_bounds__(kBlock) void k_reduce_final(const typename A::elem *__restrict__ part,
                                                          typename A::elem *__restrict__ Phi, int split,
-                                                         int64_t chunk_packs, uint32_t items)
+                                                         int64_t chunk_packs, uint32_t items, int G)
 {
     using O = Ops<A, VEC>;
     using P = typename O::P;
-    const uint32_t idx = blockIdx.x * kBlock + threadIdx.x;
-    if (idx >= items) return;
-    const P *src = reinterpret_cast<const P *>(part) + idx;
-    P acc = src[0];
-    for (int s = 1; s < split; s++) acc = O::add(acc, src[(int64_t)s * chunk_packs]);
-    reinterpret_cast<P *>(Phi)[idx] = acc;
+    __shared__ P sums[kBlock];
+    const int per_block = kBlock / G;                    // packs of this workgroup
+    const int e = threadIdx.x % per_block, g = threadIdx.x / per_block;
+    const uint32_t idx = blockIdx.x * per_block + e;
+    P acc = O::zero();
+    if (idx < items) {
+        const P *src = reinterpret_cast<const P *>(part) + idx;
+#pragma unroll 4
+        for (int s = g; s < split; s += G) acc = O::add(acc, src[(int64_t)s * chunk_packs]);
+    }
+    sums[threadIdx.x] = acc;
+    __syncthreads();
+    if (g == 0 && idx < items) {
+        for (int k = 1; k < G; k++) acc = O::add(acc, sums[k * per_block + e]);
+        reinterpret_cast<P *>(Phi)[idx] = acc;
+    }
+}
+
+// Launch geometry of k_reduce_final: more thread groups when there are few packs.
+inline int reduce_final_groups(int64_t items, int split)
+{
+    int G = 1;
+    while (G < 16 && G * 2 <= split && items * G < (1 << 18)) G *= 2;
+    return G;
 }
 
 // ------------------------------------------------------------ host helpers

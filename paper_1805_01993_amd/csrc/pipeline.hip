@@ -11,29 +11,45 @@ using namespace ccdc;
 // x (every needed element of V once), forms each sender's coded pack (written
 // to X), decodes it for each receiver exactly as k_decode does, and adds the
 // decoded pack to the receiver's running output.  Those running outputs (K nodes
-// x r segments per lane) live in LDS, one private slot per lane, so there are no
-// atomics and no barriers and the summation order is fixed.  The files a node
-// stores itself are added from V the same way.  With more than one chunk the
-// per-chunk outputs go to the workspace and k_reduce_final adds them in order.
+// x r segments per lane) live in LDS, one private slot per lane: no atomics, no
+// barriers, and since only the owning lane touches a slot the summation order is
+// program order.  (LDS float atomics were measured several times slower than
+// this read-add-write of the round's slots.)
+// The files a node stores itself are added from V the same way.  With more than
+// one chunk the per-chunk outputs go to the workspace and k_reduce_final adds
+// them in chunk order.
 //
 // LDS capacity, not registers, bounds how many wavefronts fit on a compute
 // unit, so the loads of the next PF rounds are kept in flight in registers
-// while the current round is decoded (PF = 1 and a file loop when a batch has
-// more than one file).
+// while the current round is decoded.  The round loop is branch-free so that
+// the hardware load counter can be waited on partially: a short or empty last
+// segment (RAGGED) is read at a clamped position and replaced by zeros.
+// MULTI (a batch has more than one file) adds the file loop and gives up the
+// prefetch.
+#ifndef CCDC_PIPE_PREFETCH_REGS
+#define CCDC_PIPE_PREFETCH_REGS 160               // registers a lane may spend on rounds in flight
+#endif
+#ifndef CCDC_PIPE_PREFETCH_MAX
+#define CCDC_PIPE_PREFETCH_MAX 8
+#endif
+#ifndef CCDC_PIPE_VMCNT_BUDGET
+#define CCDC_PIPE_VMCNT_BUDGET 56                 // outstanding loads+stores; the counter has 6 bits
+#endif
 template <int VEC, int R1>
 constexpr int prefetch_depth()
 {
-    constexpr int regs = VEC * R1 * (R1 - 1);      // registers one round's packs take
-    constexpr int d = 160 / regs;
-    return d < 1 ? 1 : (d > 8 ? 8 : d);
+    constexpr int by_regs = CCDC_PIPE_PREFETCH_REGS / (VEC * R1 * (R1 - 1));
+    constexpr int by_cnt = CCDC_PIPE_VMCNT_BUDGET / (R1 * (R1 - 1) + R1);
+    constexpr int d = by_regs < by_cnt ? by_regs : by_cnt;
+    return d < 1 ? 1 : (d > CCDC_PIPE_PREFETCH_MAX ? CCDC_PIPE_PREFETCH_MAX : d);
 }
 
-template <class A, int VEC, int R1, bool MULTI>
+template <class A, int VEC, int R1, bool MULTI, bool RAGGED>
 __global__ __launch_bounds__(ccdc::kPipeLanes) void k_pipeline(
     const typename A::elem *__restrict__ V, typename A::elem *__restrict__ X, typename A::elem *__restrict__ out,
     const int64_t *__restrict__ src_off, const int32_t *__restrict__ member, const int64_t *__restrict__ loc_row,
     int K, uint32_t Lv, uint32_t Wv, int m, int64_t file_stride, uint32_t R, uint32_t tiles, uint32_t chunks,
-    uint32_t n_loc, uint32_t loc_rows, int64_t chunk_stride)
+    uint32_t n_loc, int64_t chunk_stride)
 {
     using E = typename A::elem;
     using O = Ops<A, VEC>;
@@ -45,43 +61,72 @@ __global__ __launch_bounds__(ccdc::kPipeLanes) void k_pipeline(
     extern __shared__ __align__(16) unsigned char smem[];
     P *acc = reinterpret_cast<P *>(smem) + threadIdx.x;      // slot i of this lane: acc[i * LANES]
 
-    const uint32_t tile = blockIdx.x % tiles, chunk = blockIdx.x / tiles;
+    // Workgroups are handed to the 8 XCDs round-robin.  Renumber them so that each
+    // XCD gets a contiguous range of (chunk, tile) pairs: the tiles of one chunk
+    // (adjacent pieces of the same rows, the same table entries) then run next to
+    // each other in time behind one L2.
+    constexpr uint32_t XCDS = 8;
+    const uint32_t nb = gridDim.x, q = nb / XCDS, rem = nb % XCDS;
+    const uint32_t xcd = blockIdx.x % XCDS, j = blockIdx.x / XCDS;
+    const uint32_t logical = (xcd < rem ? xcd * (q + 1) : rem * (q + 1) + (xcd - rem) * q) + j;
+    const uint32_t tile = logical % tiles, chunk = logical / tiles;
     const uint32_t x = tile * LANES + threadIdx.x;
     if (x >= Lv) return;
 
     bool valid[r];                    // does segment rho reach position x (short / empty tail)
+    uint32_t offb[r];                 // byte offset of pack x of segment rho inside a packet
 #pragma unroll
-    for (int rho = 0; rho < r; rho++) valid[rho] = rho * Lv + x < Wv;
-
+    for (int rho = 0; rho < r; rho++) {
+        const uint32_t pos = rho * Lv + x;
+        valid[rho] = !RAGGED || pos < Wv;
+        offb[rho] = (valid[rho] ? pos : Wv - 1) * (uint32_t)(VEC * sizeof(E));
+    }
+    auto pack_at = [](const E *row, uint32_t byte_off) -> P {
+        return *reinterpret_cast<const P *>(reinterpret_cast<const char *>(row) + byte_off);
+    };
     for (int i = 0; i < K * r; i++) acc[i * LANES] = O::zero();
 
-    struct Stage {
-        P w[R1][r];                   // w[b][rho]: pack x of segment rho of Vbar[u][b]
+    struct Row {                      // one round's table entries (wave-uniform)
+        int64_t src[R1];              // element offset in V of packet b's first file
         int node[R1];                 // s_b
     };
-    auto issue = [&](uint32_t u, Stage &s) {
+    struct Stage {
+        P w[R1][r];                   // w[b][rho]: pack x of segment rho of Vbar[u][b]
+        int node[R1];
+    };
+    auto fetch_row = [&](uint32_t u, Row &t) {
         const int64_t *src = src_off + (size_t)u * R1;
         const int32_t *mem = member + (size_t)u * R1;
 #pragma unroll
-        for (int b = 0; b < R1; b++) s.node[b] = mem[b];
+        for (int b = 0; b < R1; b++) {
+            t.src[b] = src[b];
+            t.node[b] = mem[b];
+        }
+    };
+    auto issue = [&](const Row &t, Stage &s) {
 #pragma unroll
         for (int b = 0; b < R1; b++) {
-            const E *p0 = V + src[b] + (int64_t)x * VEC;
+            s.node[b] = t.node[b];
+            const E *row = V + t.src[b];
 #pragma unroll
             for (int rho = 0; rho < r; rho++) {
-                if (valid[rho]) {
-                    const E *q = p0 + (int64_t)rho * Lv * VEC;
-                    P t = *reinterpret_cast<const P *>(q);
-                    if constexpr (MULTI)
-                        for (int f = 1; f < m; f++) t = O::add(t, *reinterpret_cast<const P *>(q + f * file_stride));
-                    s.w[b][rho] = t;
-                } else {
-                    s.w[b][rho] = O::zero();
-                }
+                P v = pack_at(row, offb[rho]);
+                if constexpr (MULTI)
+                    for (int f = 1; f < m; f++) v = O::add(v, pack_at(row + f * file_stride, offb[rho]));
+                if constexpr (RAGGED) v = O::select(valid[rho], v, O::zero());
+                s.w[b][rho] = v;
             }
         }
     };
+    // Decode one round and add the r(r+1) decoded packs to their owners' outputs.
+    // The r(r+1) slots of a round are distinct (receiver b, segment rank(a,b)), so
+    // they are read together, updated, and written together: one LDS wait a round.
     auto consume = [&](uint32_t u, const Stage &s) {
+        P cur[R1][r];                 // cur[b][rho]: running output of node s_b, segment rho
+#pragma unroll
+        for (int b = 0; b < R1; b++)
+#pragma unroll
+            for (int rho = 0; rho < r; rho++) cur[b][rho] = acc[(s.node[b] * r + rho) * LANES];
 #pragma unroll
         for (int a = 0; a < R1; a++) {
             P coded = O::zero();
@@ -93,15 +138,18 @@ __global__ __launch_bounds__(ccdc::kPipeLanes) void k_pipeline(
             for (int b = 0; b < R1; b++) {
                 if (b == a) continue;
                 const int rho = a - (a > b ? 1 : 0);
-                if (!valid[rho]) continue;
                 P d = coded;
 #pragma unroll
                 for (int b2 = 0; b2 < R1; b2++)
                     if (b2 != a && b2 != b) d = O::sub(d, s.w[b2][a - (a > b2 ? 1 : 0)]);
-                P *slot = acc + (s.node[b] * r + rho) * LANES;
-                *slot = O::add(*slot, d);
+                // a slot past a short segment collects zeros and is never written out
+                cur[b][rho] = O::add(cur[b][rho], d);
             }
         }
+#pragma unroll
+        for (int b = 0; b < R1; b++)
+#pragma unroll
+            for (int rho = 0; rho < r; rho++) acc[(s.node[b] * r + rho) * LANES] = cur[b][rho];
     };
 
     const uint32_t u0 = (uint32_t)((uint64_t)R * chunk / chunks);
@@ -110,38 +158,48 @@ __global__ __launch_bounds__(ccdc::kPipeLanes) void k_pipeline(
     if (n > 0) {
         Stage st[PF];
 #pragma unroll
-        for (int s = 0; s < PF; s++) issue(u0 + ((uint32_t)s < n ? s : n - 1), st[s]);
+        for (int s = 0; s < PF; s++) {
+            Row t;
+            fetch_row(u0 + ((uint32_t)s < n ? s : n - 1), t);
+            issue(t, st[s]);
+        }
         for (uint32_t base = 0; base < n; base += PF) {
 #pragma unroll
             for (int s = 0; s < PF; s++) {
                 const uint32_t i = base + s;
-                if (i < n) consume(u0 + i, st[s]);
-                // keep PF rounds in flight; past the end the last round is read again
+                // keep PF rounds in flight; past the end the last round is read again.
+                // The table row is requested first so that it arrives while the
+                // current round is decoded.
                 const uint32_t nxt = i + PF;
-                issue(u0 + (nxt < n ? nxt : n - 1), st[s]);
+                Row t;
+                fetch_row(u0 + (nxt < n ? nxt : n - 1), t);
+                if (i < n) consume(u0 + i, st[s]);
+                issue(t, st[s]);
             }
         }
     }
 
-    // the files each node stores itself
+    // the files each node stores itself; a table entry is (element offset << 12) | node
     struct Own {
         P w[r];
-        uint32_t k;
+        int k;
     };
-    auto issue_own = [&](uint32_t i, Own &s) {
-        s.k = i / loc_rows;
-        const E *row = V + loc_row[i] + (int64_t)x * VEC;
-#pragma unroll
-        for (int rho = 0; rho < r; rho++)
-            s.w[rho] = valid[rho] ? *reinterpret_cast<const P *>(row + (int64_t)rho * Lv * VEC) : O::zero();
-    };
-    auto consume_own = [&](const Own &s) {
+    auto issue_own = [&](int64_t e, Own &s) {
+        s.k = (int)(e & 4095);
+        const E *row = V + (e >> 12);
 #pragma unroll
         for (int rho = 0; rho < r; rho++) {
-            if (!valid[rho]) continue;
-            P *slot = acc + (s.k * r + rho) * LANES;
-            *slot = O::add(*slot, s.w[rho]);
+            P t = pack_at(row, offb[rho]);
+            if constexpr (RAGGED) t = O::select(valid[rho], t, O::zero());
+            s.w[rho] = t;
         }
+    };
+    auto consume_own = [&](const Own &s) {
+        P cur[r];
+#pragma unroll
+        for (int rho = 0; rho < r; rho++) cur[rho] = acc[(s.k * r + rho) * LANES];
+#pragma unroll
+        for (int rho = 0; rho < r; rho++) acc[(s.k * r + rho) * LANES] = O::add(cur[rho], s.w[rho]);
     };
     const uint32_t i0 = (uint32_t)((uint64_t)n_loc * chunk / chunks);
     const uint32_t i1 = (uint32_t)((uint64_t)n_loc * (chunk + 1) / chunks);
@@ -149,24 +207,27 @@ __global__ __launch_bounds__(ccdc::kPipeLanes) void k_pipeline(
     if (nl > 0) {
         Own ow[PFL];
 #pragma unroll
-        for (int s = 0; s < PFL; s++) issue_own(i0 + ((uint32_t)s < nl ? s : nl - 1), ow[s]);
+        for (int s = 0; s < PFL; s++) issue_own(loc_row[i0 + ((uint32_t)s < nl ? s : nl - 1)], ow[s]);
         for (uint32_t base = 0; base < nl; base += PFL) {
 #pragma unroll
             for (int s = 0; s < PFL; s++) {
                 const uint32_t i = base + s;
-                if (i < nl) consume_own(ow[s]);
                 const uint32_t nxt = i + PFL;
-                issue_own(i0 + (nxt < nl ? nxt : nl - 1), ow[s]);
+                const int64_t e = loc_row[i0 + (nxt < nl ? nxt : nl - 1)];
+                if (i < nl) consume_own(ow[s]);
+                issue_own(e, ow[s]);
             }
         }
     }
 
-    E *dst = out + (int64_t)chunk * chunk_stride + (int64_t)x * VEC;
+    // write the chunk's outputs
+    E *dst = out + (int64_t)chunk * chunk_stride;
     const int64_t W = (int64_t)Wv * VEC;
     for (int k = 0; k < K; k++) {
 #pragma unroll
         for (int rho = 0; rho < r; rho++)
-            if (valid[rho]) *reinterpret_cast<P *>(dst + k * W + (int64_t)rho * Lv * VEC) = acc[(k * r + rho) * LANES];
+            if (valid[rho])
+                *reinterpret_cast<P *>(reinterpret_cast<char *>(dst + k * W) + offb[rho]) = acc[(k * r + rho) * LANES];
     }
 }
 
@@ -204,11 +265,13 @@ int launch_pipeline(const ccdc_plan_t *p, const void *V, void *X, void *Phi, hip
         kernel<<<tiles * (uint32_t)chunks, ccdc::kPipeLanes, lds, st>>>(
             (const E *)V, (E *)X, (E *)out, p->d_src_off, p->d_member, p->d_loc_row, p->K, Lv, Wv, p->m,
             (int64_t)p->Q * p->T, (uint32_t)p->nround, tiles, (uint32_t)chunks,
-            (uint32_t)(p->K * p->pipe_local_rows), (uint32_t)p->pipe_local_rows, (int64_t)p->K * p->W);
+            (uint32_t)(p->K * p->pipe_local_rows), (int64_t)p->K * p->W);
         *chunks_out = chunks;
     };
-    if (p->m > 1) go(k_pipeline<A, VEC, R1, true>);
-    else go(k_pipeline<A, VEC, R1, false>);
+    const bool ragged = p->ell * p->r != p->W;
+    if (p->m > 1) go(k_pipeline<A, VEC, R1, true, true>);
+    else if (ragged) go(k_pipeline<A, VEC, R1, false, true>);
+    else go(k_pipeline<A, VEC, R1, false, false>);
     return launched();
 }
 
@@ -228,11 +291,13 @@ int run_pipeline(const ccdc_plan_t *p, const void *V, void *X, void *Phi, bool w
     if (rc != CCDC_OK || chunks == 1) return rc;
     const int64_t n = (int64_t)p->K * p->W;
     if (wide_final) {
-        k_reduce_final<A, 4><<<cdiv(n / 4, kBlock), kBlock, 0, st>>>((const E *)p->d_workspace, (E *)Phi, chunks, n / 4,
-                                                                      (uint32_t)(n / 4));
+        const int G = reduce_final_groups(n / 4, chunks);
+        k_reduce_final<A, 4><<<cdiv(n / 4, kBlock / G), kBlock, 0, st>>>((const E *)p->d_workspace, (E *)Phi, chunks,
+                                                                          n / 4, (uint32_t)(n / 4), G);
     } else {
-        k_reduce_final<A, 1><<<cdiv(n, kBlock), kBlock, 0, st>>>((const E *)p->d_workspace, (E *)Phi, chunks, n,
-                                                                  (uint32_t)n);
+        const int G = reduce_final_groups(n, chunks);
+        k_reduce_final<A, 1><<<cdiv(n, kBlock / G), kBlock, 0, st>>>((const E *)p->d_workspace, (E *)Phi, chunks, n,
+                                                                      (uint32_t)n, G);
     }
     return launched();
 }

@@ -258,7 +258,7 @@ int bind_plan(ccdc_plan_t *p, int64_t T, int mode)
         // One-pass pipeline: single job, unrolled r, accumulators of K nodes x r
         // segments per lane must fit in LDS.  The widest pack that still leaves
         // several wavefronts per compute unit is preferred.
-        bool pipe_ok = !p->paper_jobs && r1 <= kPipeMaxR1 &&
+        bool pipe_ok = !p->paper_jobs && r1 <= kPipeMaxR1 && W < (1LL << 29) &&   // 32-bit byte offsets in a packet
                        (int64_t)p->K * r * 4 * kPipeLanes <= kPipeMaxLds;
         int pipe_vec = 1;
         int64_t pipe_cap = 1, local_rows = 0;
@@ -277,7 +277,8 @@ int bind_plan(ccdc_plan_t *p, int64_t T, int mode)
                 int64_t w = 0;
                 for (int64_t i = cnt[k]; i < cnt[k + 1]; i++)
                     if (!(rows_tab[i] & 1)) {
-                        if (w < local_rows) loc[(size_t)k * local_rows + w] = rows_tab[i] >> 1;
+                        // entry = (element offset << 12) | node; K <= 4096, offsets < 2^40
+                        if (w < local_rows) loc[(size_t)k * local_rows + w] = ((rows_tab[i] >> 1) << 12) | k;
                         w++;
                     }
                 if (w != local_rows) pipe_ok = false;

@@ -67,7 +67,10 @@ int bind_plan(ccdc_plan_t *p, int64_t T, int mode);
 // Limits of the one-pass pipeline kernel.
 constexpr int kPipeLanes = 64;                 // one wavefront per workgroup
 constexpr int kPipeMaxLds = 64 * 1024;         // bytes of LDS one workgroup may take
-constexpr int kPipeGoodLds = 26 * 1024;        // keeps >= 6 wavefronts per compute unit
+#ifndef CCDC_PIPE_GOOD_LDS
+#define CCDC_PIPE_GOOD_LDS (26 * 1024)
+#endif
+constexpr int kPipeGoodLds = CCDC_PIPE_GOOD_LDS;  // keeps >= 6 wavefronts per compute unit
 constexpr int kPipeMaxR1 = 6;                  // r+1 the kernel is unrolled for
 
 // Rank of sender a's label among the members other than b.
