@@ -26,8 +26,8 @@ __global__ __launch_bounds__(kBlock) void k_combine(const typename A::elem *__re
     if (idx >= items) return;
     const uint32_t row = idx / Wv, e = idx - row * Wv;
     const typename A::elem *src = V + src_off[row] + (int64_t)e * VEC;
-    P acc = *reinterpret_cast<const P *>(src);
-    for (int f = 1; f < m; f++) acc = O::add(acc, *reinterpret_cast<const P *>(src + f * file_stride));
+    P acc = load_stream<P>(src);
+    for (int f = 1; f < m; f++) acc = O::add(acc, load_stream<P>(src + f * file_stride));
     reinterpret_cast<P *>(Vbar)[idx] = acc;
 }
 
@@ -117,8 +117,8 @@ __global__ __launch_bounds__(kBlock) void k_shuffle_fused(const typename A::elem
         const uint32_t pos = label_rank(a, b) * Lv + x;
         if (pos >= Wv) return O::zero();
         const typename A::elem *s = V + src[b] + (int64_t)pos * VEC;
-        P acc = *reinterpret_cast<const P *>(s);
-        for (int f = 1; f < m; f++) acc = O::add(acc, *reinterpret_cast<const P *>(s + f * file_stride));
+        P acc = load_stream<P>(s);
+        for (int f = 1; f < m; f++) acc = O::add(acc, load_stream<P>(s + f * file_stride));
         return acc;
     };
 
@@ -132,7 +132,7 @@ __global__ __launch_bounds__(kBlock) void k_shuffle_fused(const typename A::elem
 #pragma unroll
         for (int b = 0; b < R1; b++)
             if (b != a) coded = O::add(coded, v[b]);
-        reinterpret_cast<P *>(X)[idx] = coded;
+        store_stream(reinterpret_cast<P *>(X) + idx, coded);
 #pragma unroll
         for (int b = 0; b < R1; b++) {
             if (b == a) continue;
@@ -142,13 +142,13 @@ __global__ __launch_bounds__(kBlock) void k_shuffle_fused(const typename A::elem
 #pragma unroll
             for (int b2 = 0; b2 < R1; b2++)
                 if (b2 != a && b2 != b) acc = O::sub(acc, v[b2]);
-            Drows[(size_t)b * Wv + pos] = acc;
+            store_stream(Drows + (size_t)b * Wv + pos, acc);
         }
     } else {
         P coded = O::zero();
         for (int b = 0; b < r1; b++)
             if (b != a) coded = O::add(coded, combined(b));
-        reinterpret_cast<P *>(X)[idx] = coded;
+        store_stream(reinterpret_cast<P *>(X) + idx, coded);
         for (int b = 0; b < r1; b++) {
             if (b == a) continue;
             const uint32_t pos = label_rank(a, b) * Lv + x;
@@ -156,7 +156,7 @@ __global__ __launch_bounds__(kBlock) void k_shuffle_fused(const typename A::elem
             P acc = coded;
             for (int b2 = 0; b2 < r1; b2++)
                 if (b2 != a && b2 != b) acc = O::sub(acc, combined(b2));
-            Drows[(size_t)b * Wv + pos] = acc;
+            store_stream(Drows + (size_t)b * Wv + pos, acc);
         }
     }
 }
@@ -191,7 +191,7 @@ __global__ __launch_bounds__(kBlock) void k_reduce_rows(const typename A::elem *
     for (int64_t i = lo; i < hi; i++) {
         const int64_t row = red_row[i];
         const typename A::elem *base = (row & 1) ? D : V;
-        acc = O::add(acc, reinterpret_cast<const P *>(base + (row >> 1))[e]);
+        acc = O::add(acc, load_stream<P>(reinterpret_cast<const P *>(base + (row >> 1)) + e));
     }
     reinterpret_cast<P *>(out + (int64_t)s * chunk_stride + red_out[o])[e] = acc;
 }

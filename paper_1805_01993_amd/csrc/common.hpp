@@ -60,6 +60,45 @@ struct Ops {
     }
 };
 
+// Streaming accesses: data that is read or written exactly once is marked
+// non-temporal so that it does not displace anything worth keeping in cache.
+#ifndef CCDC_STREAMING_HINTS
+#define CCDC_STREAMING_HINTS 1
+#endif
+template <int VEC>
+struct Bits {
+    typedef uint32_t type __attribute__((ext_vector_type(VEC)));
+};
+template <>
+struct Bits<1> {
+    typedef uint32_t type;
+};
+template <class P>
+__device__ __forceinline__ P load_stream(const void *p)
+{
+#if CCDC_STREAMING_HINTS
+    using B = typename Bits<sizeof(P) / 4>::type;
+    const B b = __builtin_nontemporal_load(reinterpret_cast<const B *>(p));
+    P out;
+    __builtin_memcpy(&out, &b, sizeof(P));
+    return out;
+#else
+    return *reinterpret_cast<const P *>(p);
+#endif
+}
+template <class P>
+__device__ __forceinline__ void store_stream(void *p, const P &v)
+{
+#if CCDC_STREAMING_HINTS
+    using B = typename Bits<sizeof(P) / 4>::type;
+    B b;
+    __builtin_memcpy(&b, &v, sizeof(P));
+    __builtin_nontemporal_store(b, reinterpret_cast<B *>(p));
+#else
+    *reinterpret_cast<P *>(p) = v;
+#endif
+}
+
 constexpr int kBlock = 256;
 
 __device__ __forceinline__ int label_rank(int a, int b) { return a - (a > b ? 1 : 0); }

@@ -82,7 +82,7 @@ __global__ __launch_bounds__(ccdc::kPipeLanes) void k_pipeline(
         offb[rho] = (valid[rho] ? pos : Wv - 1) * (uint32_t)(VEC * sizeof(E));
     }
     auto pack_at = [](const E *row, uint32_t byte_off) -> P {
-        return *reinterpret_cast<const P *>(reinterpret_cast<const char *>(row) + byte_off);
+        return load_stream<P>(reinterpret_cast<const char *>(row) + byte_off);
     };
     for (int i = 0; i < K * r; i++) acc[i * LANES] = O::zero();
 
@@ -133,7 +133,7 @@ __global__ __launch_bounds__(ccdc::kPipeLanes) void k_pipeline(
 #pragma unroll
             for (int b = 0; b < R1; b++)
                 if (b != a) coded = O::add(coded, s.w[b][a - (a > b ? 1 : 0)]);
-            reinterpret_cast<P *>(X)[((size_t)u * R1 + a) * Lv + x] = coded;
+            store_stream(reinterpret_cast<P *>(X) + ((size_t)u * R1 + a) * Lv + x, coded);
 #pragma unroll
             for (int b = 0; b < R1; b++) {
                 if (b == a) continue;
@@ -163,20 +163,24 @@ __global__ __launch_bounds__(ccdc::kPipeLanes) void k_pipeline(
             fetch_row(u0 + ((uint32_t)s < n ? s : n - 1), t);
             issue(t, st[s]);
         }
-        for (uint32_t base = 0; base < n; base += PF) {
+        // Full groups of PF rounds: no branch inside, so the compiler can wait for
+        // exactly the oldest stage and leave the younger loads in flight.  Past the
+        // end the last round is read again (never consumed).  The table row is
+        // requested before decoding so that it arrives meanwhile.
+        const uint32_t full = n / PF;
+        for (uint32_t g = 0; g < full; g++) {
 #pragma unroll
             for (int s = 0; s < PF; s++) {
-                const uint32_t i = base + s;
-                // keep PF rounds in flight; past the end the last round is read again.
-                // The table row is requested first so that it arrives while the
-                // current round is decoded.
-                const uint32_t nxt = i + PF;
+                const uint32_t i = g * PF + s, nxt = i + PF;
                 Row t;
                 fetch_row(u0 + (nxt < n ? nxt : n - 1), t);
-                if (i < n) consume(u0 + i, st[s]);
+                consume(u0 + i, st[s]);
                 issue(t, st[s]);
             }
         }
+#pragma unroll
+        for (int s = 0; s < PF; s++)
+            if (full * PF + s < n) consume(u0 + full * PF + s, st[s]);
     }
 
     // the files each node stores itself; a table entry is (element offset << 12) | node
@@ -208,16 +212,19 @@ __global__ __launch_bounds__(ccdc::kPipeLanes) void k_pipeline(
         Own ow[PFL];
 #pragma unroll
         for (int s = 0; s < PFL; s++) issue_own(loc_row[i0 + ((uint32_t)s < nl ? s : nl - 1)], ow[s]);
-        for (uint32_t base = 0; base < nl; base += PFL) {
+        const uint32_t full = nl / PFL;
+        for (uint32_t g = 0; g < full; g++) {
 #pragma unroll
             for (int s = 0; s < PFL; s++) {
-                const uint32_t i = base + s;
-                const uint32_t nxt = i + PFL;
+                const uint32_t nxt = g * PFL + s + PFL;
                 const int64_t e = loc_row[i0 + (nxt < nl ? nxt : nl - 1)];
-                if (i < nl) consume_own(ow[s]);
+                consume_own(ow[s]);
                 issue_own(e, ow[s]);
             }
         }
+#pragma unroll
+        for (int s = 0; s < PFL; s++)
+            if (full * PFL + s < nl) consume_own(ow[s]);
     }
 
     // write the chunk's outputs
