@@ -23,6 +23,37 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
 METRIC = "GB/s of intermediate values through combine+encode+decode; % of HBM peak"
 
 
+# HBM bytes per launch of the dominant kernel as the hardware counted them:
+# rocprofv3 --pmc FETCH_SIZE and --pmc WRITE_SIZE (KiB per dispatch, two runs),
+# each scaled by what the same counter reads for a device copy of 1 GiB
+# (bench.py --calibrate-copy): FETCH_SIZE reads half of the bytes there, so 2.0;
+# WRITE_SIZE reads all of them, so 1.0.  The figures hold for the kernel sources
+# whose hash is recorded with them; for any other source `traffic` is null.
+TRAFFIC = {
+    ("cfg3_gradient", "f32", "pipeline"): {
+        "source_hash": "1f8d01d3af14d834", "fetch_kib": 1419718.1, "write_kib": 1150001.7, "fetch_scale": 2.0, "write_scale": 1.0},
+    ("cfg5_k24", "f32", "pipeline"): {
+        "source_hash": "1f8d01d3af14d834", "fetch_kib": 1042218.5, "write_kib": 462096.0, "fetch_scale": 2.0, "write_scale": 1.0},
+}
+
+
+def kernel_source_hash():
+    import glob
+    import hashlib
+    h = hashlib.sha256()
+    for f in sorted(glob.glob(os.path.join(ROOT, "paper_1805_01993_amd", "csrc", "*"))):
+        with open(f, "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(workload, mode, path):
+    t = TRAFFIC.get((workload, mode, path))
+    if not t or t["source_hash"] != kernel_source_hash():
+        return None
+    return int(1024 * (t["fetch_kib"] * t["fetch_scale"] + t["write_kib"] * t["write_scale"]))
+
+
 def algorithmic_bytes_shuffle(w, ell):
     """Bytes one fused combine+encode+decode launch must move: every needed
     element of V once, every coded packet and every decoded packet once."""
@@ -73,6 +104,9 @@ def main():
                     help="pipeline: ccdc_pipeline_fused; shuffle+reduce: ccdc_shuffle_fused then ccdc_reduce")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-T", type=int, default=0)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run only a plain device copy of known size (1 GiB read + 1 GiB written per launch): "
+                         "what FETCH_SIZE / WRITE_SIZE read for it scales the counters of the other kernels")
     args = ap.parse_args()
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -90,6 +124,17 @@ def main():
         sys.exit(1)
     torch.cuda.set_device(0)
     L.load_library()
+
+    if args.calibrate_copy:
+        n = 1 << 28                                   # 2^28 fp32 = 1 GiB
+        src = torch.ones(n, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(args.warmup + args.steps):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibration": "torch copy_", "bytes_read_per_launch": 4 * n,
+                          "bytes_written_per_launch": 4 * n, "launches": args.warmup + args.steps}), flush=True)
+        return
 
     w = CONFIGS[args.workload]
     mode = args.mode or w.modes[0]
@@ -162,7 +207,8 @@ def main():
         "kernel_ms": kernel_ms,
         "roofline": {"bound": "hbm", "kernel": kernel, "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                     "algorithmic_bytes_per_launch": alg, "traffic": None},
+                     "algorithmic_bytes_per_launch": alg,
+                     "traffic": measured_traffic(w.name, mode, args.path)},
     }
     if not args.no_cpu_baseline:
         T_sample = args.cpu_sample_T or max(4, min(w.T, (1_000_000_000 // (4 * w.Q * w.N)) // 4 * 4))

@@ -113,6 +113,7 @@ class Plan:
         _check(fn(K, r, Q, N, C.byref(h)), "ccdc_plan_jobs" if jobs else "ccdc_plan")
         self._h = h
         self._lib = lib
+        self._shapes = None
 
     def close(self):
         if getattr(self, "_h", None):
@@ -128,6 +129,7 @@ class Plan:
     # ---- plan construction
     def bind(self, T, mode):
         _check(self._lib.ccdc_plan_bind(self._h, int(T), MODES.get(mode, mode)), "ccdc_plan_bind")
+        self._shapes = None
         return self
 
     def upload(self):
@@ -192,12 +194,16 @@ class Plan:
         return self.query_table(Q_PACKET_LEN, (self.r + 1,), np.int64)
 
     def shapes(self):
-        R, r1, W, ell = self.n_round, self.r + 1, self.W, self.seg_len
-        return {"V": (self.J, self.N, self.Q, self.T), "Vbar": (R, r1, W), "X": (R, r1, ell),
-                "D": (R, r1, W), "Phi": (self.J, self.Q, self.T)}
+        if self._shapes is None:          # fixed by bind(); queried once
+            R, r1, W, ell = self.n_round, self.r + 1, self.W, self.seg_len
+            self._shapes = {"V": (self.J, self.N, self.Q, self.T), "Vbar": (R, r1, W), "X": (R, r1, ell),
+                            "D": (R, r1, W), "Phi": (self.J, self.Q, self.T)}
+            self._numel = {k: int(np.prod(v)) for k, v in self._shapes.items()}
+        return self._shapes
 
     def _need(self, t, key, name):
-        want = int(np.prod(self.shapes()[key]))
+        self.shapes()
+        want = self._numel[key]
         if t.numel() != want:
             raise ValueError(f"{name}: need {want} elements, got {t.numel()}")
         return _dev_ptr(t, name)

@@ -163,10 +163,10 @@ __global__ __launch_bounds__(ccdc::kPipeLanes) void k_pipeline(
             fetch_row(u0 + ((uint32_t)s < n ? s : n - 1), t);
             issue(t, st[s]);
         }
-        // Full groups of PF rounds: no branch inside, so the compiler can wait for
-        // exactly the oldest stage and leave the younger loads in flight.  Past the
-        // end the last round is read again (never consumed).  The table row is
-        // requested before decoding so that it arrives meanwhile.
+        // Full groups of PF rounds with no branch inside (a branch makes the
+        // compiler drain every outstanding load); the remainder is handled after
+        // the loop.  Past the end the last round is read again (never consumed).
+        // The table row is requested before decoding so that it arrives meanwhile.
         const uint32_t full = n / PF;
         for (uint32_t g = 0; g < full; g++) {
 #pragma unroll

@@ -72,15 +72,19 @@ def generate_torch(J, N, Q, T, seed, mode, sigma=1.0, device="cpu"):
     out = torch.empty((J, N, Q, T), dtype=torch.float32 if mode == "f32" else torch.int32, device=device)
     i = torch.arange(T, dtype=torch.int64, device=device)[None, :]
     q = torch.arange(Q, dtype=torch.int64, device=device)[:, None]
+    q = q[None]                                       # (1, Q, 1)
+    i = i[None]                                       # (1, 1, T)
+    step = max(1, (1 << 24) // (Q * T))               # files per block: about 16M elements at a time
     for j in range(J):
-        for n in range(N):
+        for n0 in range(0, N, step):
+            n = torch.arange(n0, min(N, n0 + step), dtype=torch.int64, device=device)[:, None, None]
             ctr = ((j * Q + q) * N + n) * T + i
             h = mix(_s64(seed) + _s64(_GOLDEN) * (1 + ctr))
             if mode == "u32":
-                out[j, n] = lsr(h, 32).to(torch.int32)          # wraps: keeps the low 32 bits
+                out[j, n0:n0 + step] = lsr(h, 32).to(torch.int32)   # wraps: keeps the low 32 bits
             else:
                 u1 = (lsr(h, 40).to(torch.float64) + 1.0) / 16777216.0
                 u2 = (lsr(h, 16) & 0xFFFFFF).to(torch.float64) / 16777216.0
                 z = sigma * torch.sqrt(-2.0 * torch.log(u1)) * torch.cos(2.0 * math.pi * u2)
-                out[j, n] = z.to(torch.float32)
+                out[j, n0:n0 + step] = z.to(torch.float32)
     return out
