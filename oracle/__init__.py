@@ -17,6 +17,7 @@ from .ccdc_oracle import (  # noqa: F401
     packet_len,
     reduce,
     run_all,
+    run_all_h32,
     scheduled_elems,
     segment_count,
     segment_len,

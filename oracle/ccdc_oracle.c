@@ -313,3 +313,106 @@ int64_t orc_scheduled_elems(const orc_plan *p, int64_t T)
 #define ADD(a, b) ((a) ^ (b))
 #define SUB(a, b) ((a) ^ (b))
 #include "ccdc_oracle_stages.inc"
+
+/*
+ * Third algebra, "h32": the scheme as Sec. II narrates it for real-valued data.
+ * Pre-combining sums the intermediate values as numbers (fp32, files in
+ * ascending order, one rounding per addition); coding and decoding take the
+ * bit-wise XOR of the 32-bit patterns of the combined packets, so a receiver
+ * gets back exactly the bits of the packet meant for it; the final reduction
+ * adds numbers again (fp64 here).  Vbar and D hold fp32 values, X holds bit
+ * patterns.  Written out on its own because the three artefacts differ in
+ * type; the loops are those of ccdc_oracle_stages.inc.
+ */
+static uint32_t f32_bits(float v) { uint32_t b; memcpy(&b, &v, 4); return b; }
+static float bits_f32(uint32_t b) { float v; memcpy(&v, &b, 4); return v; }
+
+void orc_combine_h32(const orc_plan *p, int64_t T, const float *V, float *Vbar)
+{
+    const int r1 = p->r + 1;
+    const int64_t W = (int64_t)p->c * T;
+    for (int64_t u = 0; u < p->n_round; u++)
+        for (int b = 0; b < r1; b++) {
+            const int target = p->round_member[u * r1 + b];
+            const int bt = p->round_batch[u * r1 + b];
+            const int job = p->batch_job[bt], f0 = p->batch_file0[bt];
+            for (int64_t e = 0; e < W; e++) {
+                volatile float acc = 0.0f;              /* volatile: one fp32 rounding per step */
+                for (int n = f0; n < f0 + p->m; n++) {
+                    const int64_t file = (int64_t)job * p->N + n;
+                    const float v = V[(file * p->Q + (int64_t)target * p->c) * T + e];
+                    acc = (n == f0) ? v : acc + v;
+                }
+                Vbar[(u * r1 + b) * W + e] = acc;
+            }
+        }
+}
+
+void orc_encode_h32(const orc_plan *p, int64_t T, const float *Vbar, uint32_t *X)
+{
+    const int r = p->r, r1 = p->r + 1;
+    const int64_t W = (int64_t)p->c * T;
+    const int64_t ell = orc_segment_len(W, r);
+    for (int64_t u = 0; u < p->n_round; u++)
+        for (int a = 0; a < r1; a++)
+            for (int64_t x = 0; x < ell; x++) {
+                uint32_t acc = 0;
+                for (int b = 0; b < r1; b++) {
+                    if (b == a) continue;
+                    const int rho = orc_label_rank(a, b);
+                    if (x < orc_segment_count(W, r, rho)) acc ^= f32_bits(Vbar[(u * r1 + b) * W + rho * ell + x]);
+                }
+                X[(u * r1 + a) * ell + x] = acc;
+            }
+}
+
+void orc_decode_h32(const orc_plan *p, int64_t T, const uint32_t *X, const float *Vbar, float *D)
+{
+    const int r = p->r, r1 = p->r + 1;
+    const int64_t W = (int64_t)p->c * T;
+    const int64_t ell = orc_segment_len(W, r);
+    for (int64_t u = 0; u < p->n_round; u++)
+        for (int b = 0; b < r1; b++)
+            for (int a = 0; a < r1; a++) {
+                if (a == b) continue;
+                const int rho = orc_label_rank(a, b);
+                const int64_t cnt = orc_segment_count(W, r, rho);
+                for (int64_t x = 0; x < cnt; x++) {
+                    uint32_t acc = X[(u * r1 + a) * ell + x];
+                    for (int b2 = 0; b2 < r1; b2++) {
+                        if (b2 == a || b2 == b) continue;
+                        const int rho2 = orc_label_rank(a, b2);
+                        if (x < orc_segment_count(W, r, rho2))
+                            acc ^= f32_bits(Vbar[(u * r1 + b2) * W + rho2 * ell + x]);
+                    }
+                    D[(u * r1 + b) * W + rho * ell + x] = bits_f32(acc);
+                }
+            }
+}
+
+void orc_reduce_h32(const orc_plan *p, int64_t T, const float *V, const float *D, double *Phi)
+{
+    const int r = p->r, r1 = p->r + 1;
+    const int64_t W = (int64_t)p->c * T;
+    for (int64_t i = 0; i < (int64_t)p->J * p->Q * T; i++) Phi[i] = 0.0;
+    for (int64_t bt = 0; bt < p->n_batch; bt++) {
+        const int job = p->batch_job[bt];
+        for (int s = 0; s < r; s++) {
+            const int k = p->batch_label[bt * r + s];
+            double *out = Phi + ((int64_t)job * p->Q + (int64_t)k * p->c) * T;
+            for (int n = p->batch_file0[bt]; n < p->batch_file0[bt] + p->m; n++) {
+                const int64_t file = (int64_t)job * p->N + n;
+                const float *mine = V + (file * p->Q + (int64_t)k * p->c) * T;
+                for (int64_t e = 0; e < W; e++) out[e] += (double)mine[e];
+            }
+        }
+    }
+    for (int64_t u = 0; u < p->n_round; u++)
+        for (int b = 0; b < r1; b++) {
+            const int k = p->round_member[u * r1 + b];
+            const int job = p->batch_job[p->round_batch[u * r1 + b]];
+            double *out = Phi + ((int64_t)job * p->Q + (int64_t)k * p->c) * T;
+            const float *got = D + (u * r1 + b) * W;
+            for (int64_t e = 0; e < W; e++) out[e] += (double)got[e];
+        }
+}

@@ -110,6 +110,15 @@ void orc_decode_u32 (const orc_plan *p, int64_t T, const uint32_t *X, const uint
 void orc_reduce_u32 (const orc_plan *p, int64_t T, const uint32_t *V, const uint32_t *D, uint32_t *Phi);
 void orc_direct_u32 (const orc_plan *p, int64_t T, const uint32_t *V, uint32_t *Phi);  /* eq. (1) */
 
+/* The four stages, "h32" algebra: numbers are summed (fp32 when pre-combining,
+ * files ascending, one rounding per addition; fp64 in the final reduction) and
+ * packets are coded by XOR of their 32-bit patterns, as Sec. II narrates it.
+ * Vbar and D are fp32 values, X are bit patterns; D equals Vbar bit for bit. */
+void orc_combine_h32(const orc_plan *p, int64_t T, const float *V, float *Vbar);
+void orc_encode_h32 (const orc_plan *p, int64_t T, const float *Vbar, uint32_t *X);
+void orc_decode_h32 (const orc_plan *p, int64_t T, const uint32_t *X, const float *Vbar, float *D);
+void orc_reduce_h32 (const orc_plan *p, int64_t T, const float *V, const float *D, double *Phi);
+
 #ifdef __cplusplus
 }
 #endif

@@ -73,8 +73,10 @@ def _load():
     lib.orc_scheduled_elems.restype = C.c_int64
     lib.orc_scheduled_elems.argtypes = [P, C.c_int64]
     vp = C.c_void_p
-    for sfx in ("f64", "u32"):
+    for sfx in ("f64", "u32", "h32"):
         for name, nptr in (("combine", 2), ("encode", 2), ("decode", 3), ("reduce", 3), ("direct", 2)):
+            if sfx == "h32" and name == "direct":
+                continue
             fn = getattr(lib, f"orc_{name}_{sfx}")
             fn.restype = None
             fn.argtypes = [P, C.c_int64] + [vp] * nptr
@@ -239,6 +241,23 @@ def direct(plan, T, V):
     out = np.empty(sh["Phi"], dtype=el)
     getattr(_load(), f"orc_direct_{sfx}")(plan._ptr, T, _ptr(V), _ptr(out))
     return out
+
+
+def run_all_h32(plan, T, V):
+    """The "h32" algebra: fp32 sums when pre-combining, XOR of bit patterns to code
+    and decode, fp64 final reduction.  Vbar/D float32, X uint32, Phi float64."""
+    lib = _load()
+    sh = plan.shapes(T)
+    _check(V, np.float32, sh["V"], "V")
+    Vbar = np.empty(sh["Vbar"], dtype=np.float32)
+    X = np.empty(sh["X"], dtype=np.uint32)
+    D = np.zeros(sh["D"], dtype=np.float32)
+    Phi = np.empty(sh["Phi"], dtype=np.float64)
+    lib.orc_combine_h32(plan._ptr, T, _ptr(V), _ptr(Vbar))
+    lib.orc_encode_h32(plan._ptr, T, _ptr(Vbar), _ptr(X))
+    lib.orc_decode_h32(plan._ptr, T, _ptr(X), _ptr(Vbar), _ptr(D))
+    lib.orc_reduce_h32(plan._ptr, T, _ptr(V), _ptr(D), _ptr(Phi))
+    return {"Vbar": Vbar, "X": X, "D": D, "Phi": Phi}
 
 
 def run_all(plan, T, V):

@@ -228,3 +228,73 @@ def test_ragged_tail_is_zero_padded():
     assert [O.packet_len(T, 3, a) for a in range(4)] == [4, 4, 4, 2]
     assert (art["X"][0, 3, 2:] == 0).all()
     assert np.array_equal(art["Phi"], O.direct(p, T, V))
+
+
+# ------------------------------------------- "h32": real sums, XOR-coded packets
+
+def bits(a):
+    return np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
+
+
+@pytest.mark.parametrize("schedule,K,r,c,m,T", [("single", 3, 2, 1, 2, 8), ("single", 5, 2, 2, 3, 6), ("single", 4, 3, 1, 2, 10),
+                                                ("single", 6, 1, 1, 1, 5), ("paper", 4, 2, 1, 2, 12), ("paper", 5, 3, 2, 1, 7)])
+def test_h32_recovers_the_combined_packets_bit_for_bit(schedule, K, r, c, m, T):
+    """Sec. II: packets are pre-combined by summing, coded by bit-wise XOR, and every
+    node decodes 'the intended pre-combined packet' - for real-valued data the
+    decoded bits must be exactly the combined packet's, not just close."""
+    p = plan_for(K, r, c, m, schedule)
+    V = generate_numpy(p.J, p.N, p.Q, T, 21, "f32")
+    art = O.run_all_h32(p, T, V)
+    assert art["Vbar"].dtype == np.float32 and art["X"].dtype == np.uint32 and art["D"].dtype == np.float32
+    assert np.array_equal(bits(art["D"]), bits(art["Vbar"]))
+    ref = O.direct(p, T, V)
+    assert np.abs(art["Phi"] - ref).max() <= 1e-6 * np.abs(ref).max()
+    if p.m == 1:                                   # nothing is rounded: only the order of fp64 adds differs
+        assert np.abs(art["Phi"] - ref).max() <= 1e-12 * np.abs(ref).max()
+
+
+def test_h32_combine_is_the_fp32_sum_in_file_order():
+    p = O.build_plan(4, 2, 8, 18)                  # m = 3, c = 2
+    T = 5
+    V = generate_numpy(1, p.N, p.Q, T, 4, "f32")
+    Vbar = O.run_all_h32(p, T, V)["Vbar"]
+    for u in range(p.n_round):
+        for b in range(p.r + 1):
+            t = int(p.round_member[u, b])
+            f0 = int(p.batch_file0[p.round_batch[u, b]])
+            acc = V[0, f0, t * p.c:(t + 1) * p.c].reshape(-1).copy()
+            for n in range(f0 + 1, f0 + p.m):
+                acc = (acc + V[0, n, t * p.c:(t + 1) * p.c].reshape(-1)).astype(np.float32)
+            assert np.array_equal(bits(Vbar[u, b]), bits(acc))
+
+
+def test_h32_coded_packet_is_the_xor_of_labelled_segment_bits():
+    p = O.build_plan(4, 2, 4, 12)
+    T = 8
+    V = generate_numpy(1, p.N, p.Q, T, 6, "f32")
+    art = O.run_all_h32(p, T, V)
+    seg = T // p.r
+    for u in range(p.n_round):
+        S = [int(s) for s in p.round_member[u]]
+        labelled = {}
+        for b, t in enumerate(S):
+            P = tuple(s for s in S if s != t)
+            for i, node in enumerate(P):
+                labelled[(P, node)] = bits(art["Vbar"][u, b, i * seg:(i + 1) * seg])
+        for a, k in enumerate(S):
+            parts = [labelled[(P, k)] for P in combinations(S, p.r) if k in P]
+            assert np.array_equal(art["X"][u, a], np.bitwise_xor.reduce(parts, axis=0))
+
+
+def test_h32_agrees_with_the_real_algebra_on_exact_inputs():
+    """Integer-valued inputs: every sum is exact in fp32 and fp64, so the two
+    algebras must give the same packets and the same outputs."""
+    p = O.build_plan(5, 2, 5, 20)
+    T = 9
+    V = make_inputs(p, T, "f32")
+    h, f = O.run_all_h32(p, T, V), O.run_all(p, T, V)
+    assert np.array_equal(h["Vbar"].astype(np.float64), f["Vbar"])
+    assert np.array_equal(h["D"].astype(np.float64), f["D"])
+    assert np.array_equal(h["Phi"], f["Phi"])
+    # but the coded packets differ in kind: XOR of patterns is not the pattern of the sum
+    assert not np.array_equal(h["X"], bits(f["X"].astype(np.float32)))
