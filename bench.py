@@ -78,14 +78,17 @@ def cpu_baseline(w, mode, T_sample):
     import oracle as O
     from workloads import generate_numpy
 
-    op = O.build_plan(w.K, w.r, w.Q, w.N)
+    op = O.build_plan(w.K, w.r, w.Q, w.N, "paper" if w.jobs else "single")
     rng = np.random.default_rng(1)
-    if mode == "f32":
-        V = (w.sigma * rng.standard_normal((1, w.N, w.Q, T_sample), dtype=np.float32)).astype(np.float32)
+    if mode == "u32":
+        V = generate_numpy(w.J, w.N, w.Q, T_sample, 1, "u32")
     else:
-        V = generate_numpy(1, w.N, w.Q, T_sample, 1, "u32")
+        V = (w.sigma * rng.standard_normal((w.J, w.N, w.Q, T_sample), dtype=np.float32)).astype(np.float32)
     t0 = time.perf_counter()
-    O.run_all(op, T_sample, V)
+    if mode == "h32":
+        O.run_all_h32(op, T_sample, V)
+    else:
+        O.run_all(op, T_sample, V)
     dt = time.perf_counter() - t0
     return {"value": round(V.nbytes / dt / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
             "sample": f"same K,r,Q,N with T={T_sample} ({V.nbytes / 1e6:.0f} MB of intermediate values), "
@@ -138,10 +141,12 @@ def main():
 
     w = CONFIGS[args.workload]
     mode = args.mode or w.modes[0]
-    plan = L.ccdc_plan(w.K, w.r, w.Q, w.N).bind(w.T, mode).upload()
+    if w.jobs and args.path == "pipeline":
+        args.path = "shuffle+reduce"      # the one-pass kernel covers single-job plans only
+    plan = L.Plan(w.K, w.r, w.Q, w.N, jobs=w.jobs).bind(w.T, mode).upload()
     sh = plan.shapes()
-    dt = torch.float32 if mode == "f32" else torch.int32
-    V = generate_torch(1, w.N, w.Q, w.T, 1, mode, sigma=w.sigma, device="cuda")
+    dt = torch.int32 if mode == "u32" else torch.float32
+    V = generate_torch(w.J, w.N, w.Q, w.T, 1, "u32" if mode == "u32" else "f32", sigma=w.sigma, device="cuda")
     X = torch.empty(sh["X"], dtype=dt, device="cuda")
     D = torch.empty(sh["D"], dtype=dt, device="cuda") if args.path != "pipeline" else None
     Phi = torch.empty(sh["Phi"], dtype=dt, device="cuda")
@@ -187,6 +192,7 @@ def main():
         kernel, kernel_ms = "k_shuffle_fused", {"shuffle_fused": round(first_ms, 4), "reduce": round(second_ms, 4)}
         path = "ccdc_shuffle_fused + ccdc_reduce"
     achieved = alg / (first_ms * 1e-3) / 1e9
+    schedule = f"{w.J} jobs, two-stage schedule" if w.jobs else "single job"
     out = {
         "metric": METRIC,
         "value": round(value, 2),
@@ -200,7 +206,7 @@ def main():
         "vs_baseline": None,
         "dtype": mode,
         "data": "synthetic",
-        "config": {"workload": f"{w.name}: K={w.K} r={w.r} Q={w.Q} N={w.N} T={w.T} {mode}, single job, "
+        "config": {"workload": f"{w.name}: K={w.K} r={w.r} Q={w.Q} N={w.N} T={w.T} {mode}, {schedule}, "
                                f"{v_bytes / 1e9:.3f} GB of intermediate values per step",
                    "path": path},
         "pct_hbm_peak_logical": round(100 * value / HBM_PEAK_GBPS, 2),
@@ -211,7 +217,7 @@ def main():
                      "traffic": measured_traffic(w.name, mode, args.path)},
     }
     if not args.no_cpu_baseline:
-        T_sample = args.cpu_sample_T or max(4, min(w.T, (1_000_000_000 // (4 * w.Q * w.N)) // 4 * 4))
+        T_sample = args.cpu_sample_T or max(4, min(w.T, (1_000_000_000 // (4 * w.J * w.Q * w.N)) // 4 * 4))
         out["cpu_baseline"] = cpu_baseline(w, mode, T_sample)
     plan.close()
     print(json.dumps(out), flush=True)

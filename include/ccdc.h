@@ -26,8 +26,9 @@
  * 4; segment rho = [rho*ell, min(W,(rho+1)*ell)), the tail may be short/empty.
  *
  * Payload modes: CCDC_F32_SUM (fp32, real + to combine/encode/reduce, real -
- * to decode) and CCDC_U32_XOR (uint32 words of the paper's field F_{2^T},
- * + and - are both XOR; bit-exact).
+ * to decode), CCDC_U32_XOR (uint32 words of the paper's field F_{2^T},
+ * + and - are both XOR; bit-exact) and CCDC_F32_SUM_XOR (fp32 values summed,
+ * packets XOR-coded as bit patterns; decoding is bit-exact).
  *
  * Every function returns CCDC_OK (0) or a negative ccdc_status; nothing is
  * written to an output on error and the library never aborts or throws.
@@ -57,7 +58,14 @@ enum ccdc_status {
     CCDC_ESTATE = -5     /* plan not bound / not uploaded / wrong device for this call */
 };
 
-enum ccdc_mode { CCDC_F32_SUM = 0, CCDC_U32_XOR = 1 };
+enum ccdc_mode {
+    CCDC_F32_SUM = 0,       /* fp32: + to combine, encode, reduce; - to decode */
+    CCDC_U32_XOR = 1,       /* uint32 words of F_{2^T}: XOR everywhere, bit-exact */
+    CCDC_F32_SUM_XOR = 2    /* fp32 values summed when pre-combining (files ascending) and in the
+                               final reduction, packets coded and decoded by XOR of their 32-bit
+                               patterns, as Sec. II narrates the scheme: X holds bit patterns and
+                               D equals Vbar bit for bit */
+};
 
 /* Items for ccdc_plan_query.  Scalars are written as one int64_t; tables as
  * arrays of the stated type and shape. */

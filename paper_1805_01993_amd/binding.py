@@ -15,8 +15,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libccdc.so")
 
 OK, EINVAL, ENOMEM, EHIP, ESIZE, ESTATE = 0, -1, -2, -3, -4, -5
-F32_SUM, U32_XOR = 0, 1
-MODES = {"f32": F32_SUM, "u32": U32_XOR}
+F32_SUM, U32_XOR, F32_SUM_XOR = 0, 1, 2
+MODES = {"f32": F32_SUM, "u32": U32_XOR, "h32": F32_SUM_XOR}
 
 # enum ccdc_query
 (Q_K, Q_R, Q_Q, Q_N, Q_J, Q_C, Q_M, Q_NBATCH, Q_NROUND, Q_T, Q_MODE, Q_W, Q_SEG_LEN,

@@ -52,7 +52,7 @@ __global__ __launch_bounds__(kBlock) void k_encode(const typename A::elem *__res
     for (int b = 0; b < r1; b++) {
         if (b == a) continue;
         const uint32_t pos = label_rank(a, b) * Lv + x;
-        if (pos < Wv) acc = O::add(acc, rows[(size_t)b * Wv + pos]);
+        if (pos < Wv) acc = O::code(acc, rows[(size_t)b * Wv + pos]);
     }
     reinterpret_cast<P *>(X)[idx] = acc;
 }
@@ -83,7 +83,7 @@ __global__ __launch_bounds__(kBlock) void k_decode(const typename A::elem *__res
     for (int b2 = 0; b2 < r1; b2++) {
         if (b2 == a || b2 == b) continue;
         const uint32_t pos = label_rank(a, b2) * Lv + x;
-        if (pos < Wv) acc = O::sub(acc, rows[(size_t)b2 * Wv + pos]);
+        if (pos < Wv) acc = O::uncode(acc, rows[(size_t)b2 * Wv + pos]);
     }
     reinterpret_cast<P *>(D)[idx] = acc;
 }
@@ -131,7 +131,7 @@ __global__ __launch_bounds__(kBlock) void k_shuffle_fused(const typename A::elem
         P coded = O::zero();
 #pragma unroll
         for (int b = 0; b < R1; b++)
-            if (b != a) coded = O::add(coded, v[b]);
+            if (b != a) coded = O::code(coded, v[b]);
         store_stream(reinterpret_cast<P *>(X) + idx, coded);
 #pragma unroll
         for (int b = 0; b < R1; b++) {
@@ -141,13 +141,13 @@ __global__ __launch_bounds__(kBlock) void k_shuffle_fused(const typename A::elem
             P acc = coded;
 #pragma unroll
             for (int b2 = 0; b2 < R1; b2++)
-                if (b2 != a && b2 != b) acc = O::sub(acc, v[b2]);
+                if (b2 != a && b2 != b) acc = O::uncode(acc, v[b2]);
             store_stream(Drows + (size_t)b * Wv + pos, acc);
         }
     } else {
         P coded = O::zero();
         for (int b = 0; b < r1; b++)
-            if (b != a) coded = O::add(coded, combined(b));
+            if (b != a) coded = O::code(coded, combined(b));
         store_stream(reinterpret_cast<P *>(X) + idx, coded);
         for (int b = 0; b < r1; b++) {
             if (b == a) continue;
@@ -155,7 +155,7 @@ __global__ __launch_bounds__(kBlock) void k_shuffle_fused(const typename A::elem
             if (pos >= Wv) continue;
             P acc = coded;
             for (int b2 = 0; b2 < r1; b2++)
-                if (b2 != a && b2 != b) acc = O::sub(acc, combined(b2));
+                if (b2 != a && b2 != b) acc = O::uncode(acc, combined(b2));
             store_stream(Drows + (size_t)b * Wv + pos, acc);
         }
     }
@@ -322,6 +322,11 @@ int run_reduce(const ccdc_plan_t *p, const void *V, const void *D, void *Phi, hi
     do {                                                              \
         if ((p)->mode == CCDC_F32_SUM) {                              \
             using A = SumF32;                                         \
+            if ((vec) == 4) { constexpr int VEC = 4; return CALL; }   \
+            constexpr int VEC = 1;                                    \
+            return CALL;                                              \
+        } else if ((p)->mode == CCDC_F32_SUM_XOR) {                   \
+            using A = HybF32;                                         \
             if ((vec) == 4) { constexpr int VEC = 4; return CALL; }   \
             constexpr int VEC = 1;                                    \
             return CALL;                                              \

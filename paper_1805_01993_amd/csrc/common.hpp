@@ -11,17 +11,31 @@
 namespace ccdc {
 
 // ----------------------------------------------------------------- algebras
-struct SumF32 {
+// add: pre-combining and the final reduction.  code / uncode: forming a coded
+// packet and cancelling side information from it.
+struct SumF32 {                       // real numbers throughout
     using elem = float;
     static __device__ __forceinline__ elem zero() { return 0.0f; }
     static __device__ __forceinline__ elem add(elem a, elem b) { return a + b; }
-    static __device__ __forceinline__ elem sub(elem a, elem b) { return a - b; }
+    static __device__ __forceinline__ elem code(elem a, elem b) { return a + b; }
+    static __device__ __forceinline__ elem uncode(elem a, elem b) { return a - b; }
 };
-struct XorU32 {
+struct XorU32 {                       // the field F_{2^T} throughout
     using elem = uint32_t;
     static __device__ __forceinline__ elem zero() { return 0u; }
     static __device__ __forceinline__ elem add(elem a, elem b) { return a ^ b; }
-    static __device__ __forceinline__ elem sub(elem a, elem b) { return a ^ b; }
+    static __device__ __forceinline__ elem code(elem a, elem b) { return a ^ b; }
+    static __device__ __forceinline__ elem uncode(elem a, elem b) { return a ^ b; }
+};
+struct HybF32 {                       // numbers are summed, packets are XOR-coded bit patterns (Sec. II)
+    using elem = float;
+    static __device__ __forceinline__ elem zero() { return 0.0f; }    // all-zero bits: also the XOR identity
+    static __device__ __forceinline__ elem add(elem a, elem b) { return a + b; }
+    static __device__ __forceinline__ elem code(elem a, elem b)
+    {
+        return __uint_as_float(__float_as_uint(a) ^ __float_as_uint(b));
+    }
+    static __device__ __forceinline__ elem uncode(elem a, elem b) { return code(a, b); }
 };
 
 // VEC consecutive elements moved by one load/store.
@@ -46,10 +60,16 @@ struct Ops {
         for (int i = 0; i < VEC; i++) a.v[i] = A::add(a.v[i], b.v[i]);
         return a;
     }
-    static __device__ __forceinline__ P sub(P a, P b)
+    static __device__ __forceinline__ P code(P a, P b)
     {
 #pragma unroll
-        for (int i = 0; i < VEC; i++) a.v[i] = A::sub(a.v[i], b.v[i]);
+        for (int i = 0; i < VEC; i++) a.v[i] = A::code(a.v[i], b.v[i]);
+        return a;
+    }
+    static __device__ __forceinline__ P uncode(P a, P b)
+    {
+#pragma unroll
+        for (int i = 0; i < VEC; i++) a.v[i] = A::uncode(a.v[i], b.v[i]);
         return a;
     }
     static __device__ __forceinline__ P select(bool c, P a, P b)

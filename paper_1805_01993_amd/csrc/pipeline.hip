@@ -132,7 +132,7 @@ __global__ __launch_bounds__(ccdc::kPipeLanes) void k_pipeline(
             P coded = O::zero();
 #pragma unroll
             for (int b = 0; b < R1; b++)
-                if (b != a) coded = O::add(coded, s.w[b][a - (a > b ? 1 : 0)]);
+                if (b != a) coded = O::code(coded, s.w[b][a - (a > b ? 1 : 0)]);
             store_stream(reinterpret_cast<P *>(X) + ((size_t)u * R1 + a) * Lv + x, coded);
 #pragma unroll
             for (int b = 0; b < R1; b++) {
@@ -141,7 +141,7 @@ __global__ __launch_bounds__(ccdc::kPipeLanes) void k_pipeline(
                 P d = coded;
 #pragma unroll
                 for (int b2 = 0; b2 < R1; b2++)
-                    if (b2 != a && b2 != b) d = O::sub(d, s.w[b2][a - (a > b2 ? 1 : 0)]);
+                    if (b2 != a && b2 != b) d = O::uncode(d, s.w[b2][a - (a > b2 ? 1 : 0)]);
                 // a slot past a short segment collects zeros and is never written out
                 cur[b][rho] = O::add(cur[b][rho], d);
             }
@@ -328,6 +328,11 @@ int ccdc_pipeline_fused(const ccdc_plan_t *plan, const void *V, void *X, void *P
         if (vec == 4) return run_pipeline<SumF32, 4>(plan, V, X, Phi, wide_final, st);
         if (vec == 2) return run_pipeline<SumF32, 2>(plan, V, X, Phi, wide_final, st);
         return run_pipeline<SumF32, 1>(plan, V, X, Phi, wide_final, st);
+    }
+    if (plan->mode == CCDC_F32_SUM_XOR) {
+        if (vec == 4) return run_pipeline<HybF32, 4>(plan, V, X, Phi, wide_final, st);
+        if (vec == 2) return run_pipeline<HybF32, 2>(plan, V, X, Phi, wide_final, st);
+        return run_pipeline<HybF32, 1>(plan, V, X, Phi, wide_final, st);
     }
     if (vec == 4) return run_pipeline<XorU32, 4>(plan, V, X, Phi, wide_final, st);
     if (vec == 2) return run_pipeline<XorU32, 2>(plan, V, X, Phi, wide_final, st);

@@ -171,7 +171,7 @@ int build_plan(int K, int r, int Q, int N, bool paper_jobs, ccdc_plan_t **out)
 
 int bind_plan(ccdc_plan_t *p, int64_t T, int mode)
 {
-    if (!p || T < 1 || (mode != CCDC_F32_SUM && mode != CCDC_U32_XOR)) return CCDC_EINVAL;
+    if (!p || T < 1 || (mode != CCDC_F32_SUM && mode != CCDC_U32_XOR && mode != CCDC_F32_SUM_XOR)) return CCDC_EINVAL;
     const int r = p->r, r1 = r + 1;
     if (T > kMaxElems / p->c) return CCDC_ESIZE;
     const int64_t W = (int64_t)p->c * T;

@@ -80,9 +80,9 @@ def test_plan_tables_equal_the_oracles(lib, jobs):
 def test_workload_plans(lib):
     from workloads import CONFIGS
     for w in CONFIGS.values():
-        p = B.ccdc_plan(w.K, w.r, w.Q, w.N).bind(w.T, w.modes[0])
-        o = O.build_plan(w.K, w.r, w.Q, w.N)
-        assert p.n_round == w.G and p.m == w.m
+        p = B.Plan(w.K, w.r, w.Q, w.N, jobs=w.jobs).bind(w.T, w.modes[0])
+        o = O.build_plan(w.K, w.r, w.Q, w.N, "paper" if w.jobs else "single")
+        assert p.n_round == w.G and p.m == w.m and p.J == w.J
         assert np.array_equal(p.tables()["round_batch"], o.round_batch)
         assert p.scheduled_elems == O.scheduled_elems(o, w.T)
         assert p.query(B.Q_V_ELEMS) == w.v_elems

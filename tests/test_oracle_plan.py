@@ -199,5 +199,9 @@ def test_full_size_shapes():
     """Counts of the five workloads (one batch per r-subset, Q = K)."""
     from workloads import CONFIGS
     for w in CONFIGS.values():
+        if w.jobs:
+            p = O.build_plan(w.K, w.r, w.Q, w.N, "paper")
+            assert p.J == comb(w.K, w.r + 1) == w.J and p.n_round == w.G and p.m == w.m
+            continue
         p = O.build_plan(w.K, w.r, w.Q, w.N)
         assert p.n_round == comb(w.K, w.r + 1) and p.n_batch == comb(w.K, w.r) and p.m == w.m
