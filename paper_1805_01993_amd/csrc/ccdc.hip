@@ -31,6 +31,47 @@ __global__ __launch_bounds__(kBlock) void k_combine(const typename A::elem *__re
     reinterpret_cast<P *>(Vbar)[idx] = acc;
 }
 
+// Pre-combining for short packets and long batches (few packs per packet, many
+// files to add): one wavefront per packet.  The 64 lanes are cut into SEG-lane
+// segments, SEG = packs of the packet rounded up to a power of two; segment g
+// adds files g, g+G, g+2G, ... (G = 64/SEG) of the batch, each lane one pack, and
+// the G segment sums are then added across the wavefront by a butterfly of lane
+// exchanges.  The order of additions is fixed by (m, SEG), not by timing; it
+// differs from k_combine's file order, so the bit-exact h32 mode does not use it.
+template <class A, int VEC>
+__global__ __launch_bounds__(64) void k_combine_wave(const typename A::elem *__restrict__ V,
+                                                     typename A::elem *__restrict__ Vbar,
+                                                     const int64_t *__restrict__ src_off, uint32_t Wv, int seg,
+                                                     int m, int64_t file_stride, uint32_t rows)
+{
+    using E = typename A::elem;
+    using O = Ops<A, VEC>;
+    using P = typename O::P;
+    const uint32_t row = blockIdx.x;
+    if (row >= rows) return;
+    const int lane = threadIdx.x;
+    const int e = lane % seg, g = lane / seg, G = 64 / seg;
+    const E *src = V + src_off[row] + (int64_t)e * VEC;
+    P acc = O::zero();
+    if ((uint32_t)e < Wv)
+        for (int f = g; f < m; f += G) acc = O::add(acc, load_stream<P>(src + f * file_stride));
+    // segmented butterfly: after the step with distance d, lane l holds the sum of
+    // the segments whose index differs from its own only in the bits below d/seg
+    for (int d = seg; d < 64; d <<= 1) {
+        P other;
+#pragma unroll
+        for (int i = 0; i < VEC; i++) {
+            uint32_t bits;
+            __builtin_memcpy(&bits, &acc.v[i], 4);
+            bits = (uint32_t)__shfl_xor((int)bits, d, 64);
+            __builtin_memcpy(&other.v[i], &bits, 4);
+        }
+        // lower segment first on both sides so that every lane adds in the same order
+        acc = (lane & d) ? O::add(other, acc) : O::add(acc, other);
+    }
+    if (g == 0 && (uint32_t)e < Wv) reinterpret_cast<P *>(Vbar)[(size_t)row * Wv + e] = acc;
+}
+
 // ------------------------------------------------------------------- encode
 // Sec. IV-B coded packet.  One work item = one pack of X[u][a]: the sum over
 // the other members b of segment label_rank(a,b) of Vbar[u][b] at the same
@@ -242,6 +283,18 @@ int run_combine(const ccdc_plan_t *p, const void *V, void *Vbar, hipStream_t st)
     const uint32_t Wv = (uint32_t)(p->W / VEC);
     const uint64_t items = (uint64_t)p->nround * (p->r + 1) * Wv;
     if (items == 0) return CCDC_OK;
+    // short packets, long batches: a wavefront per packet with a cross-lane reduction
+#ifndef CCDC_COMBINE_WAVE_MIN_FILES
+#define CCDC_COMBINE_WAVE_MIN_FILES 8
+#endif
+    if (Wv <= 16 && p->m >= CCDC_COMBINE_WAVE_MIN_FILES && p->mode != CCDC_F32_SUM_XOR) {
+        int seg = 1;
+        while ((uint32_t)seg < Wv) seg <<= 1;
+        const uint32_t rows = (uint32_t)(p->nround * (p->r + 1));
+        k_combine_wave<A, VEC><<<rows, 64, 0, st>>>((const E *)V, (E *)Vbar, p->d_src_off, Wv, seg, p->m,
+                                                    (int64_t)p->Q * p->T, rows);
+        return launched();
+    }
     k_combine<A, VEC><<<cdiv(items, kBlock), kBlock, 0, st>>>((const E *)V, (E *)Vbar, p->d_src_off, Wv, p->m,
                                                                (int64_t)p->Q * p->T, (uint32_t)items);
     return launched();

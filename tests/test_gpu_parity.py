@@ -98,13 +98,19 @@ def run_case(torch, L, K, r, Q, N, T, mode, jobs=False, seed=1, sigma=1.0):
     torch.cuda.synchronize()
     assert_close(to_host(X2, mode), ref["X"], mode, "fused X")
     assert_close(to_host(D2, mode), ref["D"], mode, "fused D")
-    # same operation order as the separate stages: identical bits in both modes
-    assert torch.equal(X2.view(torch.int32), X.view(torch.int32))
-    assert torch.equal(D2.view(torch.int32), D.view(torch.int32))
+    # same operation order as the separate stages: identical bits in every mode, except
+    # that ccdc_combine adds short packets of long batches in a cross-lane tree (fp32 only)
+    W = (Q // K) * T
+    tree_combine = mode == "f32" and op.m >= 8 and W // (4 if T % 4 == 0 else 1) <= 16
+    if not tree_combine:
+        assert torch.equal(X2.view(torch.int32), X.view(torch.int32))
+        assert torch.equal(D2.view(torch.int32), D.view(torch.int32))
     Phi2 = dev_empty(torch, sh["Phi"], mode, poison)
     plan.reduce(V, D2, Phi2)
     torch.cuda.synchronize()
-    assert torch.equal(Phi2.view(torch.int32), Phi.view(torch.int32))
+    if not tree_combine:
+        assert torch.equal(Phi2.view(torch.int32), Phi.view(torch.int32))
+    assert_close(to_host(Phi2, mode), ref_phi, mode, "Phi from fused D vs eq.(1)")
 
     # the whole path in one pass (single-job plans, r <= 5, K*r <= 256)
     X3 = dev_empty(torch, sh["X"], mode, poison)
@@ -112,7 +118,8 @@ def run_case(torch, L, K, r, Q, N, T, mode, jobs=False, seed=1, sigma=1.0):
     if not jobs and r <= 5 and K * r <= 256:
         plan.pipeline_fused(V, X3, Phi3)
         torch.cuda.synchronize()
-        assert torch.equal(X3.view(torch.int32), X.view(torch.int32))
+        assert torch.equal(X3.view(torch.int32), X2.view(torch.int32))
+        assert_close(to_host(X3, mode), ref["X"], mode, "pipeline X")
         assert_close(to_host(Phi3, mode), ref["Phi"], mode, "pipeline Phi")
         assert_close(to_host(Phi3, mode), ref_phi, mode, "pipeline Phi vs eq.(1)")
     else:
@@ -152,6 +159,10 @@ EDGE = [
     (4, 2, 4, 6, 512, True),      # paper's 4-job running example shape
     (5, 2, 10, 6, 258, True),     # J = 10 jobs, c = 2, scalar path
     (6, 3, 6, 8, 1200, True),     # J = 15 jobs, m = 2
+    (4, 2, 4, 240, 12, False),    # short packets, m = 40: wavefront-wide combiner, 3 packs in segments of 4
+    (4, 2, 8, 96, 5, False),      # same with c = 2, scalar packs: 10 packs in segments of 16, m = 16
+    (4, 2, 4, 48, 8, True),       # same under the J-job schedule: 2 packs, m = 16
+    (5, 1, 5, 45, 64, False),     # m = 9 with exactly 16 packs
 ]
 
 
