@@ -5,6 +5,7 @@ tests, the smoke check and the benchmark's CPU-baseline leg have an
 independent answer to compare with.
 """
 from .ccdc_oracle import (  # noqa: F401
+    CompressionPlan,
     OraclePlan,
     build_library,
     build_plan,

@@ -416,3 +416,81 @@ void orc_reduce_h32(const orc_plan *p, int64_t T, const float *V, const float *D
             for (int64_t e = 0; e < W; e++) out[e] += (double)got[e];
         }
 }
+
+/* ------------------------------------------------------------------------
+ * Compression-only comparison scheme (appendix of the paper).
+ */
+void orc_cplan_free(orc_cplan *p)
+{
+    if (!p) return;
+    free(p->batch_first); free(p->node_batch); free(p->pkt_recv); free(p->pkt_batch); free(p->pkt_send);
+    free(p);
+}
+
+orc_cplan *orc_cplan_build(int K, int r, int Q, int N)
+{
+    if (K < 2 || r < 1 || r > K - 1 || Q < 1 || N < 1 || Q % K != 0 || K > N) return NULL;
+    /* mu = r/K; storage beyond one half of the files is not used by this scheme */
+    int num = r, den = K;
+    if (2 * r > K) { num = 1; den = 2; }
+    if (((int64_t)N * num) % den != 0) return NULL;          /* mu*N files per batch */
+    const int per = (int)((int64_t)N * num / den);
+    const int nb = (den + num - 1) / num;                    /* ceil(1/mu) */
+    orc_cplan *p = (orc_cplan *)calloc(1, sizeof(orc_cplan));
+    if (!p) return NULL;
+    p->K = K; p->r = r; p->Q = Q; p->N = N; p->c = Q / K; p->nb = nb;
+    p->n_packet = (int64_t)K * (nb - 1);
+    p->batch_first = (int *)malloc(sizeof(int) * (size_t)(nb + 1));
+    p->node_batch = (int *)malloc(sizeof(int) * (size_t)K);
+    p->pkt_recv = (int *)malloc(sizeof(int) * (size_t)(p->n_packet > 0 ? p->n_packet : 1));
+    p->pkt_batch = (int *)malloc(sizeof(int) * (size_t)(p->n_packet > 0 ? p->n_packet : 1));
+    p->pkt_send = (int *)malloc(sizeof(int) * (size_t)(p->n_packet > 0 ? p->n_packet : 1));
+    if (!p->batch_first || !p->node_batch || !p->pkt_recv || !p->pkt_batch || !p->pkt_send) {
+        orc_cplan_free(p);
+        return NULL;
+    }
+    for (int t = 0; t < nb; t++) p->batch_first[t] = t * per;    /* the last batch takes the rest */
+    p->batch_first[nb] = N;
+    for (int k = 0; k < K; k++) p->node_batch[k] = k % nb;
+    int64_t i = 0;
+    for (int k = 0; k < K; k++)
+        for (int t = 0; t < nb; t++) {
+            if (t == p->node_batch[k]) continue;
+            int sender = -1;                                     /* next node after k that stores B_t */
+            for (int d = 1; d < K && sender < 0; d++)
+                if (p->node_batch[(k + d) % K] == t) sender = (k + d) % K;
+            if (sender < 0) { orc_cplan_free(p); return NULL; }
+            p->pkt_recv[i] = k; p->pkt_batch[i] = t; p->pkt_send[i] = sender;
+            i++;
+        }
+    return p;
+}
+
+int64_t orc_cplan_scheduled_elems(const orc_cplan *p, int64_t T)
+{
+    return p->n_packet * (int64_t)p->c * T;
+}
+
+#undef FN
+#undef TIN
+#undef TEL
+#undef ZERO
+#undef ADD
+#undef SUB
+#define FN(name) CAT(name, _f64)
+#define TIN float
+#define TEL double
+#define ZERO 0.0
+#define ADD(a, b) ((a) + (b))
+#include "ccdc_oracle_compression.inc"
+#undef FN
+#undef TIN
+#undef TEL
+#undef ZERO
+#undef ADD
+#define FN(name) CAT(name, _u32)
+#define TIN uint32_t
+#define TEL uint32_t
+#define ZERO 0u
+#define ADD(a, b) ((a) ^ (b))
+#include "ccdc_oracle_compression.inc"

@@ -119,6 +119,36 @@ void orc_encode_h32 (const orc_plan *p, int64_t T, const float *Vbar, uint32_t *
 void orc_decode_h32 (const orc_plan *p, int64_t T, const uint32_t *X, const float *Vbar, float *D);
 void orc_reduce_h32 (const orc_plan *p, int64_t T, const float *V, const float *D, double *Phi);
 
+/*
+ * Comparison scheme "compression only" (appendix of the paper): one job, no
+ * coding.  With mu = r/K (taken as 1/2 when larger: more storage does not help
+ * this scheme) the files are cut into nb = ceil(1/mu) consecutive batches, the
+ * first nb-1 of mu*N files, the last of the rest; node k stores batch k mod nb.
+ * For every node k and every batch t it does not store, one node that stores
+ * B_t (the next one after k, cyclically) pre-combines the c values k reduces
+ * and sends that packet to k.  P[n_packet][W] holds the packets, receiver-major,
+ * batches ascending; Phi[Q][T].
+ */
+typedef struct orc_cplan {
+    int K, r, Q, N, c;
+    int nb;              /* batches */
+    int *batch_first;    /* [nb+1] file ranges */
+    int *node_batch;     /* [K] batch stored by node k */
+    int64_t n_packet;    /* K * (nb-1) */
+    int *pkt_recv;       /* [n_packet] receiving node */
+    int *pkt_batch;      /* [n_packet] batch the packet pre-combines */
+    int *pkt_send;       /* [n_packet] node that sends it (stores pkt_batch) */
+} orc_cplan;
+
+/* NULL on invalid parameters (as orc_plan_build, and mu*N must be whole). */
+orc_cplan *orc_cplan_build(int K, int r, int Q, int N);
+void orc_cplan_free(orc_cplan *p);
+int64_t orc_cplan_scheduled_elems(const orc_cplan *p, int64_t T);
+void orc_ccombine_f64(const orc_cplan *p, int64_t T, const float *V, double *P);
+void orc_creduce_f64 (const orc_cplan *p, int64_t T, const float *V, const double *P, double *Phi);
+void orc_ccombine_u32(const orc_cplan *p, int64_t T, const uint32_t *V, uint32_t *P);
+void orc_creduce_u32 (const orc_cplan *p, int64_t T, const uint32_t *V, const uint32_t *P, uint32_t *Phi);
+
 #ifdef __cplusplus
 }
 #endif

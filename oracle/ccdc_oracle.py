@@ -16,7 +16,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SO = os.path.join(_HERE, "libccdc_oracle.so")
 _SRCS = ["ccdc_oracle.c"]
-_DEPS = ["ccdc_oracle.c", "ccdc_oracle.h", "ccdc_oracle_stages.inc"]
+_DEPS = ["ccdc_oracle.c", "ccdc_oracle.h", "ccdc_oracle_stages.inc", "ccdc_oracle_compression.inc"]
 
 
 def build_library(force: bool = False) -> str:
@@ -241,6 +241,71 @@ def direct(plan, T, V):
     out = np.empty(sh["Phi"], dtype=el)
     getattr(_load(), f"orc_direct_{sfx}")(plan._ptr, T, _ptr(V), _ptr(out))
     return out
+
+
+class _CCPlan(C.Structure):
+    _fields_ = [
+        ("K", C.c_int), ("r", C.c_int), ("Q", C.c_int), ("N", C.c_int), ("c", C.c_int), ("nb", C.c_int),
+        ("batch_first", C.POINTER(C.c_int)), ("node_batch", C.POINTER(C.c_int)),
+        ("n_packet", C.c_int64),
+        ("pkt_recv", C.POINTER(C.c_int)), ("pkt_batch", C.POINTER(C.c_int)), ("pkt_send", C.POINTER(C.c_int)),
+    ]
+
+
+class CompressionPlan:
+    """Placement and packet list of the compression-only comparison scheme (appendix)."""
+
+    def __init__(self, K, r, Q, N):
+        lib = _load()
+        lib.orc_cplan_build.restype = C.POINTER(_CCPlan)
+        lib.orc_cplan_build.argtypes = [C.c_int] * 4
+        lib.orc_cplan_free.restype = None
+        lib.orc_cplan_free.argtypes = [C.POINTER(_CCPlan)]
+        lib.orc_cplan_scheduled_elems.restype = C.c_int64
+        lib.orc_cplan_scheduled_elems.argtypes = [C.POINTER(_CCPlan), C.c_int64]
+        for sfx in ("f64", "u32"):
+            for name, nptr in (("ccombine", 2), ("creduce", 3)):
+                fn = getattr(lib, f"orc_{name}_{sfx}")
+                fn.restype = None
+                fn.argtypes = [C.POINTER(_CCPlan), C.c_int64] + [C.c_void_p] * nptr
+        ptr = lib.orc_cplan_build(K, r, Q, N)
+        if not ptr:
+            raise ValueError(f"invalid parameters K={K} r={r} Q={Q} N={N}")
+        self._ptr, self._lib = ptr, lib
+        s = ptr.contents
+        self.K, self.r, self.Q, self.N, self.c, self.nb = s.K, s.r, s.Q, s.N, s.c, s.nb
+        self.n_packet = int(s.n_packet)
+        self.batch_first = _arr(s.batch_first, (self.nb + 1,))
+        self.node_batch = _arr(s.node_batch, (self.K,))
+        self.pkt_recv = _arr(s.pkt_recv, (self.n_packet,))
+        self.pkt_batch = _arr(s.pkt_batch, (self.n_packet,))
+        self.pkt_send = _arr(s.pkt_send, (self.n_packet,))
+
+    def __del__(self):
+        try:
+            if self._ptr:
+                self._lib.orc_cplan_free(self._ptr)
+                self._ptr = None
+        except Exception:
+            pass
+
+    def scheduled_elems(self, T):
+        return int(self._lib.orc_cplan_scheduled_elems(self._ptr, T))
+
+    def combine(self, T, V):
+        sfx, el = _mode(V)
+        _check(V, np.float32 if sfx == "f64" else np.uint32, (self.N, self.Q, T), "V")
+        out = np.empty((self.n_packet, self.c * T), dtype=el)
+        getattr(self._lib, f"orc_ccombine_{sfx}")(self._ptr, T, _ptr(V), _ptr(out))
+        return out
+
+    def reduce(self, T, V, P):
+        sfx, el = _mode(V)
+        _check(V, np.float32 if sfx == "f64" else np.uint32, (self.N, self.Q, T), "V")
+        _check(P, el, (self.n_packet, self.c * T), "P")
+        out = np.empty((self.Q, T), dtype=el)
+        getattr(self._lib, f"orc_creduce_{sfx}")(self._ptr, T, _ptr(V), _ptr(P), _ptr(out))
+        return out
 
 
 def run_all_h32(plan, T, V):
