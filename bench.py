@@ -78,21 +78,28 @@ def cpu_baseline(w, mode, T_sample):
     import oracle as O
     from workloads import generate_numpy
 
-    op = O.build_plan(w.K, w.r, w.Q, w.N, "paper" if w.jobs else "single")
+    op = None if w.compression else O.build_plan(w.K, w.r, w.Q, w.N, "paper" if w.jobs else "single")
     rng = np.random.default_rng(1)
     if mode == "u32":
         V = generate_numpy(w.J, w.N, w.Q, T_sample, 1, "u32")
     else:
         V = (w.sigma * rng.standard_normal((w.J, w.N, w.Q, T_sample), dtype=np.float32)).astype(np.float32)
-    t0 = time.perf_counter()
-    if mode == "h32":
-        O.run_all_h32(op, T_sample, V)
-    else:
-        O.run_all(op, T_sample, V)
-    dt = time.perf_counter() - t0
-    return {"value": round(V.nbytes / dt / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
+    cp = O.CompressionPlan(w.K, w.r, w.Q, w.N) if w.compression else None
+    reps, dt = 0, 0.0
+    while dt < 10.0 and reps < 64:         # whole passes over the sample until about 10 s have gone
+        t0 = time.perf_counter()
+        if w.compression:
+            cp.reduce(T_sample, V[0], cp.combine(T_sample, V[0]))
+        elif mode == "h32":
+            O.run_all_h32(op, T_sample, V)
+        else:
+            O.run_all(op, T_sample, V)
+        dt += time.perf_counter() - t0
+        reps += 1
+    return {"value": round(reps * V.nbytes / dt / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
             "sample": f"same K,r,Q,N with T={T_sample} ({V.nbytes / 1e6:.0f} MB of intermediate values), "
-                      f"all four stages, {dt:.1f} s",
+                      f"{'combine and reduce' if w.compression else 'all four stages'}, "
+                      f"{reps} passes in {dt:.1f} s",
             "host_cpus": os.cpu_count()}
 
 
@@ -143,7 +150,9 @@ def main():
     mode = args.mode or w.modes[0]
     if w.jobs and args.path == "pipeline":
         args.path = "shuffle+reduce"      # the one-pass kernel covers single-job plans only
-    plan = L.Plan(w.K, w.r, w.Q, w.N, jobs=w.jobs).bind(w.T, mode).upload()
+    if w.compression:
+        args.path = "combine+reduce"      # the comparison scheme codes nothing
+    plan = L.Plan(w.K, w.r, w.Q, w.N, jobs=w.jobs, compression=w.compression).bind(w.T, mode).upload()
     sh = plan.shapes()
     dt = torch.int32 if mode == "u32" else torch.float32
     V = generate_torch(w.J, w.N, w.Q, w.T, 1, "u32" if mode == "u32" else "f32", sigma=w.sigma, device="cuda")
@@ -159,6 +168,11 @@ def main():
             plan.pipeline_fused(V, X, Phi, stream=stream)
             if events is not None:
                 events[1].record(stream)
+        elif args.path == "combine+reduce":
+            plan.combine(V, D, stream=stream)          # D: the uncoded packets, sent as they are
+            if events is not None:
+                events[1].record(stream)
+            plan.reduce(V, D, Phi, stream=stream)
         else:
             plan.shuffle_fused(V, X, D, stream=stream)
             if events is not None:
@@ -187,12 +201,21 @@ def main():
         alg = algorithmic_bytes_pipeline(w, plan.seg_len)
         kernel, kernel_ms = "k_pipeline (+ k_reduce_final when the rounds are chunked)", {"pipeline_fused": round(first_ms, 4)}
         path = "ccdc_pipeline_fused"
+    elif args.path == "combine+reduce":
+        # every packet reads the files of its batch once and is written once
+        rows_files = sum(int(n) for n in
+                         (plan.compression_tables()["batch_first"][1:] - plan.compression_tables()["batch_first"][:-1])
+                         [plan.compression_tables()["pkt_batch"]])
+        alg = 4 * w.W * (rows_files + plan.query(L.binding.Q_NROWS))
+        kernel, kernel_ms = "k_combine", {"combine": round(first_ms, 4), "reduce": round(second_ms, 4)}
+        path = "ccdc_combine + ccdc_reduce (compression-only comparison scheme)"
     else:
         alg = algorithmic_bytes_shuffle(w, plan.seg_len)
         kernel, kernel_ms = "k_shuffle_fused", {"shuffle_fused": round(first_ms, 4), "reduce": round(second_ms, 4)}
         path = "ccdc_shuffle_fused + ccdc_reduce"
     achieved = alg / (first_ms * 1e-3) / 1e9
-    schedule = f"{w.J} jobs, two-stage schedule" if w.jobs else "single job"
+    schedule = (f"{w.J} jobs, two-stage schedule" if w.jobs else
+                "single job, compression-only comparison scheme" if w.compression else "single job")
     out = {
         "metric": METRIC,
         "value": round(value, 2),

@@ -72,7 +72,7 @@ enum ccdc_mode {
 enum ccdc_query {
     CCDC_Q_K = 0, CCDC_Q_R, CCDC_Q_Q, CCDC_Q_N, CCDC_Q_J, CCDC_Q_C, CCDC_Q_M,
     CCDC_Q_NBATCH,           /* batches over all jobs */
-    CCDC_Q_NROUND,           /* rounds R */
+    CCDC_Q_NROUND,           /* rounds R (K for ccdc_plan_compression) */
     CCDC_Q_T, CCDC_Q_MODE, CCDC_Q_W,                 /* need a bound plan from here on */
     CCDC_Q_SEG_LEN,          /* ell */
     CCDC_Q_SCHEDULED_ELEMS,  /* elements all coded packets really carry */
@@ -85,7 +85,14 @@ enum ccdc_query {
     CCDC_Q_BATCH_FILE0,      /* int32_t[NBATCH]    first file (index inside its job)    */
     CCDC_Q_BATCH_LABEL,      /* int32_t[NBATCH][r] nodes storing the batch, ascending   */
     CCDC_Q_ROUND_MEMBER,     /* int32_t[R][r+1]    nodes of the round, ascending        */
-    CCDC_Q_ROUND_BATCH       /* int32_t[R][r+1]    batch served to member b             */
+    CCDC_Q_ROUND_BATCH,      /* int32_t[R][r+1]    batch served to member b             */
+    CCDC_Q_NROWS = 128,      /* packets = rows of Vbar and D: R*(r+1), or K*(nb-1) uncoded      */
+    CCDC_Q_SCHEME,           /* 0 ccdc_plan, 1 ccdc_plan_jobs, 2 ccdc_plan_compression          */
+    CCDC_Q_BATCH_FIRST,      /* int32_t[NBATCH+1]  file ranges of the batches   (compression)   */
+    CCDC_Q_NODE_BATCH,       /* int32_t[K]         batch stored by node k       (compression)   */
+    CCDC_Q_PACKET_RECV,      /* int32_t[NROWS]     receiver of packet i         (compression)   */
+    CCDC_Q_PACKET_BATCH,     /* int32_t[NROWS]     batch packet i pre-combines  (compression)   */
+    CCDC_Q_PACKET_SEND       /* int32_t[NROWS]     node that sends packet i     (compression)   */
 };
 
 /*
@@ -105,6 +112,20 @@ enum ccdc_query {
  */
 int ccdc_plan(int K, int r, int Q, int N, ccdc_plan_t **out);
 int ccdc_plan_jobs(int K, int r, int Q, int N, ccdc_plan_t **out);
+
+/*
+ * The comparison scheme that only pre-combines (appendix of the paper), one job,
+ * nothing coded: with mu = r/K (taken as 1/2 when larger) the files are cut into
+ * nb = ceil(1/mu) consecutive batches of mu*N files (the last takes the rest),
+ * node k stores batch k mod nb, and for every node k and every batch t it does
+ * not store, the next node after k (cyclically) that stores B_t pre-combines the
+ * values of k's c functions and sends that packet.  Vbar = D = [K*(nb-1)][W]
+ * (receiver-major, batches ascending) are the packets; there is no X.  Only
+ * ccdc_combine and ccdc_reduce (called with D = Vbar) apply; the coding entry
+ * points return CCDC_ESTATE.  Its load is ceil(1/mu)-1 (mu < 1/2) or 1 (Sec. III).
+ * Errors as ccdc_plan, with "batch count divides N" replaced by "mu*N is whole".
+ */
+int ccdc_plan_compression(int K, int r, int Q, int N, ccdc_plan_t **out);
 void ccdc_plan_destroy(ccdc_plan_t *plan);   /* frees host and device parts; NULL is fine */
 
 /*

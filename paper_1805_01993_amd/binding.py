@@ -23,9 +23,10 @@ MODES = {"f32": F32_SUM, "u32": U32_XOR, "h32": F32_SUM_XOR}
  Q_SCHEDULED_ELEMS, Q_CLOSED_FORM_NUM, Q_CLOSED_FORM_DEN, Q_V_ELEMS, Q_VBAR_ELEMS, Q_X_ELEMS,
  Q_D_ELEMS, Q_PHI_ELEMS, Q_WORKSPACE_BYTES) = range(22)
 (Q_PACKET_LEN, Q_BATCH_JOB, Q_BATCH_FILE0, Q_BATCH_LABEL, Q_ROUND_MEMBER, Q_ROUND_BATCH) = range(64, 70)
+(Q_NROWS, Q_SCHEME, Q_BATCH_FIRST, Q_NODE_BATCH, Q_PACKET_RECV, Q_PACKET_BATCH, Q_PACKET_SEND) = range(128, 135)
 
 EXPORTS = [
-    "ccdc_plan", "ccdc_plan_jobs", "ccdc_plan_destroy", "ccdc_plan_bind", "ccdc_plan_upload",
+    "ccdc_plan", "ccdc_plan_jobs", "ccdc_plan_compression", "ccdc_plan_destroy", "ccdc_plan_bind", "ccdc_plan_upload",
     "ccdc_plan_query", "ccdc_strerror", "ccdc_combine", "ccdc_encode", "ccdc_decode", "ccdc_reduce",
     "ccdc_shuffle_fused", "ccdc_pipeline_fused",
 ]
@@ -59,6 +60,8 @@ def load_library():
     lib.ccdc_plan.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, C.POINTER(vp)]
     lib.ccdc_plan_jobs.restype = C.c_int
     lib.ccdc_plan_jobs.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, C.POINTER(vp)]
+    lib.ccdc_plan_compression.restype = C.c_int
+    lib.ccdc_plan_compression.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, C.POINTER(vp)]
     lib.ccdc_plan_destroy.restype = None
     lib.ccdc_plan_destroy.argtypes = [vp]
     lib.ccdc_plan_bind.restype = C.c_int
@@ -106,12 +109,13 @@ def _stream_ptr(stream):
 class Plan:
     """Owns one ccdc_plan_t.  Methods mirror the C entry points."""
 
-    def __init__(self, K, r, Q, N, jobs=False):
+    def __init__(self, K, r, Q, N, jobs=False, compression=False):
         lib = load_library()
         h = C.c_void_p()
-        fn = lib.ccdc_plan_jobs if jobs else lib.ccdc_plan
-        _check(fn(K, r, Q, N, C.byref(h)), "ccdc_plan_jobs" if jobs else "ccdc_plan")
+        name = "ccdc_plan_compression" if compression else ("ccdc_plan_jobs" if jobs else "ccdc_plan")
+        _check(getattr(lib, name)(K, r, Q, N, C.byref(h)), name)
         self._h = h
+        self.compression = bool(compression)
         self._lib = lib
         self._shapes = None
 
@@ -191,13 +195,28 @@ class Plan:
         }
 
     def packet_len(self):
-        return self.query_table(Q_PACKET_LEN, (self.r + 1,), np.int64)
+        return self.query_table(Q_PACKET_LEN, (1 if self.compression else self.r + 1,), np.int64)
+
+    def compression_tables(self):
+        nb, rows = self.n_batch, self.query(Q_NROWS)
+        return {
+            "batch_first": self.query_table(Q_BATCH_FIRST, (nb + 1,), np.int32),
+            "node_batch": self.query_table(Q_NODE_BATCH, (self.K,), np.int32),
+            "pkt_recv": self.query_table(Q_PACKET_RECV, (rows,), np.int32),
+            "pkt_batch": self.query_table(Q_PACKET_BATCH, (rows,), np.int32),
+            "pkt_send": self.query_table(Q_PACKET_SEND, (rows,), np.int32),
+        }
 
     def shapes(self):
         if self._shapes is None:          # fixed by bind(); queried once
             R, r1, W, ell = self.n_round, self.r + 1, self.W, self.seg_len
-            self._shapes = {"V": (self.J, self.N, self.Q, self.T), "Vbar": (R, r1, W), "X": (R, r1, ell),
-                            "D": (R, r1, W), "Phi": (self.J, self.Q, self.T)}
+            if self.compression:          # uncoded packets only: K receivers x (nb-1) batches
+                rows = self.query(Q_NROWS)
+                self._shapes = {"V": (1, self.N, self.Q, self.T), "Vbar": (rows, W), "X": (0,),
+                                "D": (rows, W), "Phi": (1, self.Q, self.T)}
+            else:
+                self._shapes = {"V": (self.J, self.N, self.Q, self.T), "Vbar": (R, r1, W), "X": (R, r1, ell),
+                                "D": (R, r1, W), "Phi": (self.J, self.Q, self.T)}
             self._numel = {k: int(np.prod(v)) for k, v in self._shapes.items()}
         return self._shapes
 
@@ -243,3 +262,8 @@ def ccdc_plan(K, r, Q, N):
 def ccdc_plan_jobs(K, r, Q, N):
     """The paper's J = C(K, r+1)-job placement and two-stage schedule."""
     return Plan(K, r, Q, N, jobs=True)
+
+
+def ccdc_plan_compression(K, r, Q, N):
+    """The compression-only comparison scheme (appendix): cyclic batches, uncoded packets."""
+    return Plan(K, r, Q, N, compression=True)

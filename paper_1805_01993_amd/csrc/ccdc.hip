@@ -13,11 +13,13 @@ using namespace ccdc;
 
 // ------------------------------------------------------------------ combine
 // Sec. IV-B pre-combining.  One work item = one pack of one packet Vbar[u][b]:
-// it adds the same pack of the m files of the served batch.
+// it adds the same pack of the files of the served batch (m of them, or
+// row_files[row] when batches differ in size).
 template <class A, int VEC>
 __global__ __launch_bounds__(kBlock) void k_combine(const typename A::elem *__restrict__ V,
                                                     typename A::elem *__restrict__ Vbar,
-                                                    const int64_t *__restrict__ src_off, uint32_t Wv, int m,
+                                                    const int64_t *__restrict__ src_off,
+                                                    const int32_t *__restrict__ row_files, uint32_t Wv, int m,
                                                     int64_t file_stride, uint32_t items)
 {
     using O = Ops<A, VEC>;
@@ -26,8 +28,9 @@ __global__ __launch_bounds__(kBlock) void k_combine(const typename A::elem *__re
     if (idx >= items) return;
     const uint32_t row = idx / Wv, e = idx - row * Wv;
     const typename A::elem *src = V + src_off[row] + (int64_t)e * VEC;
+    const int files = row_files ? row_files[row] : m;
     P acc = load_stream<P>(src);
-    for (int f = 1; f < m; f++) acc = O::add(acc, load_stream<P>(src + f * file_stride));
+    for (int f = 1; f < files; f++) acc = O::add(acc, load_stream<P>(src + f * file_stride));
     reinterpret_cast<P *>(Vbar)[idx] = acc;
 }
 
@@ -251,11 +254,13 @@ void release_device(ccdc_plan_t *p)
         (void)hipFree(p->d_red_out);
         (void)hipFree(p->d_loc_row);
         (void)hipFree(p->d_member);
+        (void)hipFree(p->d_row_files);
         (void)hipFree(p->d_workspace);
         if (sw) (void)hipSetDevice(cur);
     }
     p->d_src_off = p->d_red_ptr = p->d_red_row = p->d_red_out = p->d_loc_row = nullptr;
     p->d_member = nullptr;
+    p->d_row_files = nullptr;
     p->d_workspace = nullptr;
     p->uploaded = false;
     p->device = -1;
@@ -281,22 +286,22 @@ int run_combine(const ccdc_plan_t *p, const void *V, void *Vbar, hipStream_t st)
 {
     using E = typename A::elem;
     const uint32_t Wv = (uint32_t)(p->W / VEC);
-    const uint64_t items = (uint64_t)p->nround * (p->r + 1) * Wv;
+    const uint64_t items = (uint64_t)p->nrows * Wv;
     if (items == 0) return CCDC_OK;
     // short packets, long batches: a wavefront per packet with a cross-lane reduction
 #ifndef CCDC_COMBINE_WAVE_MIN_FILES
 #define CCDC_COMBINE_WAVE_MIN_FILES 8
 #endif
-    if (Wv <= 16 && p->m >= CCDC_COMBINE_WAVE_MIN_FILES && p->mode != CCDC_F32_SUM_XOR) {
+    if (Wv <= 16 && p->m >= CCDC_COMBINE_WAVE_MIN_FILES && p->mode != CCDC_F32_SUM_XOR && !p->d_row_files) {
         int seg = 1;
         while ((uint32_t)seg < Wv) seg <<= 1;
-        const uint32_t rows = (uint32_t)(p->nround * (p->r + 1));
+        const uint32_t rows = (uint32_t)p->nrows;
         k_combine_wave<A, VEC><<<rows, 64, 0, st>>>((const E *)V, (E *)Vbar, p->d_src_off, Wv, seg, p->m,
                                                     (int64_t)p->Q * p->T, rows);
         return launched();
     }
-    k_combine<A, VEC><<<cdiv(items, kBlock), kBlock, 0, st>>>((const E *)V, (E *)Vbar, p->d_src_off, Wv, p->m,
-                                                               (int64_t)p->Q * p->T, (uint32_t)items);
+    k_combine<A, VEC><<<cdiv(items, kBlock), kBlock, 0, st>>>((const E *)V, (E *)Vbar, p->d_src_off, p->d_row_files,
+                                                               Wv, p->m, (int64_t)p->Q * p->T, (uint32_t)items);
     return launched();
 }
 
@@ -400,6 +405,11 @@ int ccdc_plan(int K, int r, int Q, int N, ccdc_plan_t **out) { return ccdc::buil
 
 int ccdc_plan_jobs(int K, int r, int Q, int N, ccdc_plan_t **out) { return ccdc::build_plan(K, r, Q, N, true, out); }
 
+int ccdc_plan_compression(int K, int r, int Q, int N, ccdc_plan_t **out)
+{
+    return ccdc::build_compression_plan(K, r, Q, N, out);
+}
+
 void ccdc_plan_destroy(ccdc_plan_t *plan)
 {
     if (!plan) return;
@@ -432,6 +442,7 @@ int ccdc_plan_upload(ccdc_plan_t *plan)
     if (rc == CCDC_OK) rc = to_device(plan->red_out, &plan->d_red_out);
     if (rc == CCDC_OK) rc = to_device(plan->loc_row, &plan->d_loc_row);
     if (rc == CCDC_OK) rc = to_device(plan->round_member, &plan->d_member);
+    if (rc == CCDC_OK && !plan->row_files.empty()) rc = to_device(plan->row_files, &plan->d_row_files);
     if (rc == CCDC_OK && plan->workspace_bytes > 0 &&
         hipMalloc(&plan->d_workspace, plan->workspace_bytes) != hipSuccess) {
         plan->d_workspace = nullptr;
@@ -470,6 +481,13 @@ int ccdc_plan_query(const ccdc_plan_t *p, int what, void *out, size_t out_bytes)
     case CCDC_Q_M: return scalar(p->m);
     case CCDC_Q_NBATCH: return scalar(p->nbatch);
     case CCDC_Q_NROUND: return scalar(p->nround);
+    case CCDC_Q_NROWS: return scalar(p->nrows);
+    case CCDC_Q_SCHEME: return scalar(p->compression ? 2 : (p->paper_jobs ? 1 : 0));
+    case CCDC_Q_BATCH_FIRST: return table(p->batch_first.data(), p->batch_first.size() * 4);
+    case CCDC_Q_NODE_BATCH: return table(p->node_batch.data(), p->node_batch.size() * 4);
+    case CCDC_Q_PACKET_RECV: return table(p->pkt_recv.data(), p->pkt_recv.size() * 4);
+    case CCDC_Q_PACKET_BATCH: return table(p->pkt_batch.data(), p->pkt_batch.size() * 4);
+    case CCDC_Q_PACKET_SEND: return table(p->pkt_send.data(), p->pkt_send.size() * 4);
     case CCDC_Q_BATCH_JOB: return table(p->batch_job.data(), p->batch_job.size() * 4);
     case CCDC_Q_BATCH_FILE0: return table(p->batch_file0.data(), p->batch_file0.size() * 4);
     case CCDC_Q_BATCH_LABEL: return table(p->batch_label.data(), p->batch_label.size() * 4);
@@ -494,12 +512,12 @@ int ccdc_plan_query(const ccdc_plan_t *p, int what, void *out, size_t out_bytes)
     case CCDC_Q_W: return scalar(p->W);
     case CCDC_Q_SEG_LEN: return scalar(p->ell);
     case CCDC_Q_SCHEDULED_ELEMS: return scalar(p->scheduled);
-    case CCDC_Q_CLOSED_FORM_NUM: return scalar(p->nround * r1 * p->W);
-    case CCDC_Q_CLOSED_FORM_DEN: return scalar(p->r);
+    case CCDC_Q_CLOSED_FORM_NUM: return scalar(p->compression ? p->nrows * p->W : p->nround * r1 * p->W);
+    case CCDC_Q_CLOSED_FORM_DEN: return scalar(p->compression ? 1 : p->r);
     case CCDC_Q_V_ELEMS: return scalar((int64_t)p->J * p->N * p->Q * p->T);
-    case CCDC_Q_VBAR_ELEMS: return scalar(p->nround * r1 * p->W);
-    case CCDC_Q_X_ELEMS: return scalar(p->nround * r1 * p->ell);
-    case CCDC_Q_D_ELEMS: return scalar(p->nround * r1 * p->W);
+    case CCDC_Q_VBAR_ELEMS: return scalar(p->nrows * p->W);
+    case CCDC_Q_X_ELEMS: return scalar(p->compression ? 0 : p->nrows * p->ell);
+    case CCDC_Q_D_ELEMS: return scalar(p->nrows * p->W);
     case CCDC_Q_PHI_ELEMS: return scalar((int64_t)p->J * p->Q * p->T);
     case CCDC_Q_WORKSPACE_BYTES: return scalar((int64_t)p->workspace_bytes);
     case CCDC_Q_PACKET_LEN: return table(p->packet_len.data(), p->packet_len.size() * 8);
@@ -533,6 +551,7 @@ int ccdc_encode(const ccdc_plan_t *plan, const void *Vbar, void *X, void *stream
 {
     int rc = ready(plan), vec = 1;
     if (rc != CCDC_OK) return rc;
+    if (plan->compression) return CCDC_ESTATE;       // nothing is coded in that scheme
     if ((rc = pick_vec(plan, &vec, Vbar, (const void *)X)) != CCDC_OK) return rc;
     hipStream_t st = (hipStream_t)stream;
     CCDC_DISPATCH(plan, vec, (run_encode<A, VEC>(plan, Vbar, X, st)));
@@ -542,6 +561,7 @@ int ccdc_decode(const ccdc_plan_t *plan, const void *X, const void *Vbar, void *
 {
     int rc = ready(plan), vec = 1;
     if (rc != CCDC_OK) return rc;
+    if (plan->compression) return CCDC_ESTATE;       // nothing is coded in that scheme
     if ((rc = pick_vec(plan, &vec, X, Vbar, (const void *)D)) != CCDC_OK) return rc;
     hipStream_t st = (hipStream_t)stream;
     CCDC_DISPATCH(plan, vec, (run_decode<A, VEC>(plan, X, Vbar, D, st)));
@@ -560,6 +580,7 @@ int ccdc_shuffle_fused(const ccdc_plan_t *plan, const void *V, void *X, void *D,
 {
     int rc = ready(plan), vec = 1;
     if (rc != CCDC_OK) return rc;
+    if (plan->compression) return CCDC_ESTATE;       // nothing is coded in that scheme
     if ((rc = pick_vec(plan, &vec, V, (const void *)X, (const void *)D)) != CCDC_OK) return rc;
     hipStream_t st = (hipStream_t)stream;
     CCDC_DISPATCH(plan, vec, (run_shuffle<A, VEC>(plan, V, X, D, st)));

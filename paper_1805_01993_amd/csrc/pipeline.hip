@@ -317,6 +317,7 @@ int ccdc_pipeline_fused(const ccdc_plan_t *plan, const void *V, void *X, void *P
 {
     int rc = ready(plan), vec4 = 1;
     if (rc != CCDC_OK) return rc;
+    if (plan->compression) return CCDC_ESTATE;       // nothing is coded in that scheme
     if (!plan->pipe_ok) return CCDC_ESIZE;
     if ((rc = pick_vec(plan, &vec4, V, (const void *)X, (const void *)Phi)) != CCDC_OK) return rc;
     // widest pack allowed by the plan's LDS budget and by the pointers

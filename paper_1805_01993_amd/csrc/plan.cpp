@@ -90,6 +90,7 @@ int build_plan(int K, int r, int Q, int N, bool paper_jobs, ccdc_plan_t **out)
         p->J = paper_jobs ? (int)G : 1;
         p->nbatch = nbatch;
         p->nround = nround;
+        p->nrows = nround * r1;
         p->batch_job.resize((size_t)nbatch);
         p->batch_file0.resize((size_t)nbatch);
         p->batch_label.resize((size_t)nbatch * r);
@@ -169,9 +170,118 @@ int build_plan(int K, int r, int Q, int N, bool paper_jobs, ccdc_plan_t **out)
     return CCDC_OK;
 }
 
+// Compression-only comparison scheme (appendix of the paper): no coding.  With
+// mu = r/K (taken as 1/2 when larger) the files are cut into nb = ceil(1/mu)
+// consecutive batches of mu*N files (the last takes the rest), node k stores
+// batch k mod nb, and for every node k and batch t it does not store, the next
+// node after k (cyclically) that stores B_t pre-combines and sends one packet.
+int build_compression_plan(int K, int r, int Q, int N, ccdc_plan_t **out)
+{
+    if (!out) return CCDC_EINVAL;
+    *out = nullptr;
+    if (K < 2 || r < 1 || r > K - 1 || Q < 1 || N < 1 || Q % K != 0 || K > N) return CCDC_EINVAL;
+    if (K > 4096) return CCDC_ESIZE;
+    int64_t num = r, den = K;
+    if (2 * r > K) { num = 1; den = 2; }                   // more than half the files does not help here
+    if (((int64_t)N * num) % den != 0) return CCDC_EINVAL;  // mu*N files per batch
+    const int64_t per = (int64_t)N * num / den;
+    const int nb = (int)((den + num - 1) / num);
+    ccdc_plan_t *p = new (std::nothrow) ccdc_plan_t;
+    if (!p) return CCDC_ENOMEM;
+    try {
+        p->K = K; p->r = r; p->Q = Q; p->N = N;
+        p->c = Q / K;
+        p->m = (int)per;
+        p->compression = true;
+        p->J = 1;
+        p->nbatch = nb;
+        p->nround = K;                                     // one group of packets per receiver
+        p->nrows = (int64_t)K * (nb - 1);
+        p->batch_first.resize((size_t)nb + 1);
+        for (int t = 0; t < nb; t++) p->batch_first[t] = (int32_t)(t * per);
+        p->batch_first[nb] = N;
+        p->batch_job.assign((size_t)nb, 0);
+        p->batch_file0.assign(p->batch_first.begin(), p->batch_first.end() - 1);
+        p->node_batch.resize((size_t)K);
+        for (int k = 0; k < K; k++) p->node_batch[k] = k % nb;
+        for (int k = 0; k < K; k++)
+            for (int t = 0; t < nb; t++) {
+                if (t == p->node_batch[k]) continue;
+                int sender = -1;
+                for (int d = 1; d < K && sender < 0; d++)
+                    if (p->node_batch[(k + d) % K] == t) sender = (k + d) % K;
+                p->pkt_recv.push_back(k);
+                p->pkt_batch.push_back(t);
+                p->pkt_send.push_back(sender);
+                p->row_files.push_back(p->batch_first[t + 1] - p->batch_first[t]);
+            }
+    } catch (const std::bad_alloc &) {
+        delete p;
+        return CCDC_ENOMEM;
+    }
+    *out = p;
+    return CCDC_OK;
+}
+
+namespace {
+
+// ccdc_plan_bind for the compression-only scheme: the packet is sent whole (no
+// segments), so ell = W, and every packet is both what is transmitted and what
+// the receiver adds.
+int bind_compression(ccdc_plan_t *p, int64_t T, int mode)
+{
+    if (T > kMaxElems / p->c) return CCDC_ESIZE;
+    const int64_t W = (int64_t)p->c * T;
+    const int vec = (T % 4 == 0) ? 4 : 1;
+    if ((double)p->N * p->Q * (double)T > (double)kMaxElems || (double)p->nrows * (double)W > (double)kMaxElems)
+        return CCDC_ESIZE;
+    if ((double)std::max<int64_t>(p->nrows, p->K) * (double)((W + vec - 1) / vec) > (double)kMaxItems) return CCDC_ESIZE;
+    try {
+        std::vector<int64_t> src((size_t)p->nrows);
+        for (int64_t i = 0; i < p->nrows; i++)
+            src[i] = ((int64_t)p->batch_first[p->pkt_batch[i]] * p->Q + (int64_t)p->pkt_recv[i] * p->c) * T;
+        // reduce lists: own batch from V, then the received packets in order
+        const int64_t nout = p->K;
+        std::vector<int64_t> ptr((size_t)nout + 1, 0), rows, outs((size_t)nout);
+        int64_t min_rows = std::numeric_limits<int64_t>::max();
+        for (int k = 0; k < p->K; k++) {
+            const int j = p->node_batch[k];
+            for (int n = p->batch_first[j]; n < p->batch_first[j + 1]; n++)
+                rows.push_back((((int64_t)n * p->Q + (int64_t)k * p->c) * T) << 1);
+            for (int64_t i = 0; i < p->nrows; i++)
+                if (p->pkt_recv[i] == k) rows.push_back(((i * W) << 1) | 1);
+            ptr[k + 1] = (int64_t)rows.size();
+            outs[k] = (int64_t)k * W;
+            min_rows = std::min(min_rows, ptr[k + 1] - ptr[k]);
+        }
+        const int64_t items = nout * ((W + vec - 1) / vec);
+        int64_t split = 1;
+        if (items < (1 << 18)) split = std::min<int64_t>({(int64_t)256, std::max<int64_t>(1, min_rows), ((1 << 19) + items - 1) / items});
+        p->T = T; p->W = W; p->ell = W; p->mode = mode;
+        p->packet_len.assign(1, W);
+        p->scheduled = p->nrows * W;
+        p->src_off.swap(src);
+        p->red_ptr.swap(ptr);
+        p->red_row.swap(rows);
+        p->red_out.swap(outs);
+        p->nout = nout;
+        p->red_split = (int)split;
+        p->workspace_bytes = split > 1 ? (size_t)split * (size_t)p->Q * (size_t)T * 4 : 0;
+        p->pipe_ok = false;
+        p->loc_row.clear();
+        p->bound = true;
+    } catch (const std::bad_alloc &) {
+        return CCDC_ENOMEM;
+    }
+    return CCDC_OK;
+}
+
+}  // namespace
+
 int bind_plan(ccdc_plan_t *p, int64_t T, int mode)
 {
     if (!p || T < 1 || (mode != CCDC_F32_SUM && mode != CCDC_U32_XOR && mode != CCDC_F32_SUM_XOR)) return CCDC_EINVAL;
+    if (p->compression) return bind_compression(p, T, mode);
     const int r = p->r, r1 = r + 1;
     if (T > kMaxElems / p->c) return CCDC_ESIZE;
     const int64_t W = (int64_t)p->c * T;

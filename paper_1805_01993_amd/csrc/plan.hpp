@@ -15,7 +15,16 @@ struct ccdc_plan_s {
     int c = 0;            // Q / K functions per node
     int m = 0;            // files per batch
     bool paper_jobs = false;
+    bool compression = false;           // uncoded comparison scheme (appendix): combine + reduce only
     int64_t nbatch = 0, nround = 0;
+    int64_t nrows = 0;                  // packets: rows of Vbar and of D (nround*(r+1) for coded plans)
+
+    // compression-only scheme: consecutive batches, node k stores batch k mod nbatch,
+    // one uncoded packet per (receiver, batch it does not store)
+    std::vector<int32_t> batch_first;   // [nbatch+1]
+    std::vector<int32_t> node_batch;    // [K]
+    std::vector<int32_t> pkt_recv, pkt_batch, pkt_send;   // [nrows]
+    std::vector<int32_t> row_files;     // [nrows] files added into each packet (batches differ in size)
 
     // placement (Sec. IV-A) and rounds (Sec. IV-B)
     std::vector<int32_t> batch_job;     // [nbatch]
@@ -55,6 +64,7 @@ struct ccdc_plan_s {
     int64_t *d_src_off = nullptr, *d_red_ptr = nullptr, *d_red_row = nullptr, *d_red_out = nullptr;
     int64_t *d_loc_row = nullptr;
     int32_t *d_member = nullptr;
+    int32_t *d_row_files = nullptr;     // null when every packet adds m files
     void *d_workspace = nullptr;
 };
 
@@ -62,6 +72,7 @@ namespace ccdc {
 
 // Host-side construction; both return a ccdc_status.
 int build_plan(int K, int r, int Q, int N, bool paper_jobs, ccdc_plan_t **out);
+int build_compression_plan(int K, int r, int Q, int N, ccdc_plan_t **out);
 int bind_plan(ccdc_plan_t *p, int64_t T, int mode);
 
 // Limits of the one-pass pipeline kernel.

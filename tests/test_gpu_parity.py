@@ -324,3 +324,38 @@ def test_full_size_gradient_workload(torch, L):
 def test_full_size_paper_schedule(torch, L, mode):
     """J = 56 jobs on K = 8 nodes, stage 1 and the five stage-2 rounds of every subset."""
     full_size_case(torch, L, "jobs_k8", mode, n_rounds=12)
+
+
+# ------------------------------------- compression-only comparison scheme
+
+@pytest.mark.parametrize("K,r,c,N,T", [(4, 2, 1, 6, 1024), (8, 2, 1, 28, 4096), (7, 2, 2, 14, 333), (6, 1, 1, 12, 520),
+                                       (5, 3, 1, 10, 7), (9, 2, 1, 36, 64)])
+@pytest.mark.parametrize("mode", ["u32", "f32"])
+def test_compression_scheme(torch, L, K, r, c, N, T, mode):
+    """Uncoded pre-combined packets (appendix): ccdc_combine makes them, ccdc_reduce
+    adds them to the receiver's own batch; the coding entry points refuse the plan."""
+    Q = c * K
+    cp = O.CompressionPlan(K, r, Q, N)
+    Vh = generate_numpy(1, N, Q, T, K + r, mode)
+    want_p = cp.combine(T, Vh[0])
+    want_phi = cp.reduce(T, Vh[0], want_p)
+    plan = L.ccdc_plan_compression(K, r, Q, N).bind(T, mode).upload()
+    sh = plan.shapes()
+    V = to_dev(torch, Vh)
+    poison = -1 if mode == "u32" else float("nan")
+    P = dev_empty(torch, sh["Vbar"], mode, poison)
+    Phi = dev_empty(torch, sh["Phi"], mode, poison)
+    plan.combine(V, P)
+    plan.reduce(V, P, Phi)
+    torch.cuda.synchronize()
+    assert_close(to_host(P, mode), want_p, mode, "packets")
+    assert_close(to_host(Phi, mode)[0], want_phi, mode, "Phi")
+    direct = np.bitwise_xor.reduce(Vh[0], axis=0) if mode == "u32" else Vh[0].sum(axis=0, dtype=np.float64)
+    assert_close(to_host(Phi, mode)[0], direct, mode, "Phi vs eq.(1)")
+    import ctypes as C
+    lib, ptr = L.load_library(), C.c_void_p(P.data_ptr())
+    assert lib.ccdc_encode(plan._h, ptr, ptr, None) == L.binding.ESTATE
+    assert lib.ccdc_decode(plan._h, ptr, ptr, ptr, None) == L.binding.ESTATE
+    assert lib.ccdc_shuffle_fused(plan._h, ptr, ptr, ptr, None) == L.binding.ESTATE
+    assert lib.ccdc_pipeline_fused(plan._h, ptr, ptr, ptr, None) == L.binding.ESTATE
+    plan.close()

@@ -80,6 +80,8 @@ def test_plan_tables_equal_the_oracles(lib, jobs):
 def test_workload_plans(lib):
     from workloads import CONFIGS
     for w in CONFIGS.values():
+        if w.compression:
+            continue                      # covered by test_compression_plan_tables_equal_the_oracles
         p = B.Plan(w.K, w.r, w.Q, w.N, jobs=w.jobs).bind(w.T, w.modes[0])
         o = O.build_plan(w.K, w.r, w.Q, w.N, "paper" if w.jobs else "single")
         assert p.n_round == w.G and p.m == w.m and p.J == w.J
@@ -146,3 +148,46 @@ def test_product_path_never_imports_the_oracle():
             if f.endswith((".py", ".hip", ".cpp", ".hpp", ".h")):
                 text = open(os.path.join(dirpath, f)).read()
                 assert "oracle" not in text.lower().replace("no cpu fallback", ""), f
+
+
+def test_compression_plan_tables_equal_the_oracles(lib):
+    n = 0
+    for K in range(2, 10):
+        for r in range(1, K):
+            for c in (1, 2):
+                N = 2 * K * r
+                p = B.ccdc_plan_compression(K, r, c * K, N)
+                o = O.CompressionPlan(K, r, c * K, N)
+                assert p.query(B.Q_SCHEME) == 2 and p.n_batch == o.nb and p.query(B.Q_NROWS) == o.n_packet
+                for name, tab in p.compression_tables().items():
+                    assert np.array_equal(tab, getattr(o, name)), (K, r, name)
+                for T in (1, 6, 8):
+                    p.bind(T, "u32")
+                    assert p.W == c * T and p.seg_len == c * T
+                    assert p.scheduled_elems == o.scheduled_elems(T) == p.closed_form_elems
+                    assert p.packet_len().tolist() == [c * T]
+                    assert p.shapes()["Vbar"] == (o.n_packet, c * T) and p.query(B.Q_X_ELEMS) == 0
+                p.close()
+                n += 1
+    assert n == 72
+    h = C.c_void_p()
+    assert lib.ccdc_plan_compression(5, 2, 5, 6, C.byref(h)) == B.EINVAL      # mu*N not whole
+    assert lib.ccdc_plan_compression(4, 3, 4, 5, C.byref(h)) == B.EINVAL      # mu > 1/2 needs even N
+    assert lib.ccdc_plan_compression(4, 2, 4, 8, None) == B.EINVAL
+
+
+def test_load_comparison_reproduces_the_papers_remark(lib, golden):
+    """Remark after the K = 4 example: 3/4 (compressed CDC), 1 (combining only), 3/2 (CDC only)."""
+    from fractions import Fraction
+
+    from paper_1805_01993_amd.loads import comparison
+    g = golden("example_k4.txt")
+    rows = comparison(int(g["K"]), int(g["r"]), int(g["Q"]), int(g["N"]))
+    assert rows["compressed CDC (Theorem 1, J jobs)"] == Fraction(g["load_total"])
+    assert rows["compression only (appendix)"] == Fraction(g["load_compression_only"])
+    assert rows["CDC only (formula of Sec. III)"] == Fraction(g["load_cdc_only"])
+    # a shape whose N fits only some schemes still answers for the others
+    rows = comparison(8, 2, 8, 28)
+    assert rows["compressed CDC (Theorem 1, J jobs)"] is None
+    assert rows["compressed CDC, single-job schedule"] == Fraction(21, 2)
+    assert rows["compression only (appendix)"] == 3

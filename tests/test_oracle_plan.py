@@ -199,6 +199,10 @@ def test_full_size_shapes():
     """Counts of the five workloads (one batch per r-subset, Q = K)."""
     from workloads import CONFIGS
     for w in CONFIGS.values():
+        if w.compression:
+            cp = O.CompressionPlan(w.K, w.r, w.Q, w.N)
+            assert cp.nb == 4 and cp.n_packet == 24
+            continue
         if w.jobs:
             p = O.build_plan(w.K, w.r, w.Q, w.N, "paper")
             assert p.J == comb(w.K, w.r + 1) == w.J and p.n_round == w.G and p.m == w.m

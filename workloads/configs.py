@@ -23,6 +23,7 @@ class Workload:
     sigma: float    # std of the fp32 values
     modes: tuple    # payload modes the shape is run in
     jobs: bool = False   # True: the paper's J-job schedule; False: one job over the whole cluster
+    compression: bool = False   # True: the uncoded compression-only comparison scheme (appendix)
 
     @property
     def c(self):
@@ -62,6 +63,8 @@ CONFIGS = {
     "cfg4_k16": Workload("cfg4_k16", 16, 3, 16, 560, 4096, 1.0, ("f32",)),
     "cfg5_k24": Workload("cfg5_k24", 24, 4, 24, 10626, 2048, 1.0, ("f32", "u32", "h32")),
     "jobs_k8": Workload("jobs_k8", 8, 2, 8, 9, 150_000, 1.0, ("f32", "u32"), jobs=True),
+    # the gradient shape through the compression-only comparison scheme (4 batches of 7 files)
+    "comp_gradient": Workload("comp_gradient", 8, 2, 8, 28, 3_200_000, 0.01, ("f32",), compression=True),
 }
 
 
