@@ -13,11 +13,15 @@ from .ccdc_oracle import (  # noqa: F401
     combine,
     decode,
     direct,
+    direct_h16,
     encode,
+    h16_narrow,
+    h16_widen,
     label_rank,
     packet_len,
     reduce,
     run_all,
+    run_all_h16,
     run_all_h32,
     scheduled_elems,
     segment_count,

@@ -6,6 +6,7 @@
  */
 #include "ccdc_oracle.h"
 
+#include <math.h>
 #include <stdlib.h>
 #include <string.h>
 
@@ -494,3 +495,8 @@ int64_t orc_cplan_scheduled_elems(const orc_cplan *p, int64_t T)
 #define ZERO 0u
 #define ADD(a, b) ((a) ^ (b))
 #include "ccdc_oracle_compression.inc"
+
+/* ------------------------------------------------------------------------
+ * Hybrid scheme for 16-bit floating-point payloads.
+ */
+#include "ccdc_oracle_h16.inc"

@@ -149,6 +149,20 @@ void orc_creduce_f64 (const orc_cplan *p, int64_t T, const float *V, const doubl
 void orc_ccombine_u32(const orc_cplan *p, int64_t T, const uint32_t *V, uint32_t *P);
 void orc_creduce_u32 (const orc_cplan *p, int64_t T, const uint32_t *V, const uint32_t *P, uint32_t *Phi);
 
+/* The four stages, "h16" algebra: the hybrid scheme for 16-bit floating-point
+ * payloads (fmt 0 = bfloat16, 1 = IEEE binary16), every artefact a 16-bit
+ * pattern.  Pre-combining adds in fp32 (files ascending) and rounds the sum
+ * once to the format, to nearest even; packets are coded by XOR of their
+ * patterns; the final reduction is exact fp64 arithmetic on the 16-bit values
+ * and is not rounded.  D equals Vbar bit for bit. */
+void orc_h16_widen (const uint16_t *in, float *out, int64_t n, int fmt);      /* exact */
+void orc_h16_narrow(const float *in, uint16_t *out, int64_t n, int fmt);      /* nearest, ties to even */
+void orc_combine_h16(const orc_plan *p, int64_t T, int fmt, const uint16_t *V, uint16_t *Vbar);
+void orc_encode_h16 (const orc_plan *p, int64_t T, const uint16_t *Vbar, uint16_t *X);
+void orc_decode_h16 (const orc_plan *p, int64_t T, const uint16_t *X, const uint16_t *Vbar, uint16_t *D);
+void orc_reduce_h16 (const orc_plan *p, int64_t T, int fmt, const uint16_t *V, const uint16_t *D, double *Phi);
+void orc_direct_h16 (const orc_plan *p, int64_t T, int fmt, const uint16_t *V, double *Phi);   /* eq. (1) */
+
 #ifdef __cplusplus
 }
 #endif

@@ -16,7 +16,8 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SO = os.path.join(_HERE, "libccdc_oracle.so")
 _SRCS = ["ccdc_oracle.c"]
-_DEPS = ["ccdc_oracle.c", "ccdc_oracle.h", "ccdc_oracle_stages.inc", "ccdc_oracle_compression.inc"]
+_DEPS = ["ccdc_oracle.c", "ccdc_oracle.h", "ccdc_oracle_stages.inc", "ccdc_oracle_compression.inc",
+         "ccdc_oracle_h16.inc"]
 
 
 def build_library(force: bool = False) -> str:
@@ -27,7 +28,7 @@ def build_library(force: bool = False) -> str:
         stale = any(os.path.getmtime(os.path.join(_HERE, d)) > so_time for d in _DEPS)
     if stale:
         cmd = ["gcc", "-std=c11", "-O2", "-Wall", "-Wextra", "-fPIC", "-shared",
-               "-o", _SO] + [os.path.join(_HERE, s) for s in _SRCS]
+               "-o", _SO] + [os.path.join(_HERE, s) for s in _SRCS] + ["-lm"]
         subprocess.run(cmd, check=True, cwd=_HERE)
     return _SO
 
@@ -332,3 +333,51 @@ def run_all(plan, T, V):
     D = decode(plan, T, X, Vbar)
     Phi = reduce(plan, T, V, D)
     return {"Vbar": Vbar, "X": X, "D": D, "Phi": Phi}
+
+
+H16_FORMATS = {"bf16": 0, "f16": 1}
+
+
+def h16_widen(bits, fmt):
+    """Exact float32 values of 16-bit patterns (fmt "bf16" or "f16")."""
+    bits = np.ascontiguousarray(bits, dtype=np.uint16)
+    out = np.empty(bits.shape, dtype=np.float32)
+    lib = _load()
+    lib.orc_h16_widen(_ptr(bits), _ptr(out), C.c_int64(bits.size), H16_FORMATS[fmt])
+    return out
+
+
+def h16_narrow(values, fmt):
+    """Nearest 16-bit patterns (ties to even) of float32 values."""
+    values = np.ascontiguousarray(values, dtype=np.float32)
+    out = np.empty(values.shape, dtype=np.uint16)
+    lib = _load()
+    lib.orc_h16_narrow(_ptr(values), _ptr(out), C.c_int64(values.size), H16_FORMATS[fmt])
+    return out
+
+
+def run_all_h16(plan, T, V, fmt):
+    """The "h16" algebra on 16-bit patterns V (uint16): Vbar/X/D uint16, Phi float64 (not rounded)."""
+    lib = _load()
+    f = H16_FORMATS[fmt]
+    sh = plan.shapes(T)
+    _check(V, np.uint16, sh["V"], "V")
+    Vbar = np.empty(sh["Vbar"], dtype=np.uint16)
+    X = np.empty(sh["X"], dtype=np.uint16)
+    D = np.zeros(sh["D"], dtype=np.uint16)
+    Phi = np.empty(sh["Phi"], dtype=np.float64)
+    T64 = C.c_int64(T)
+    lib.orc_combine_h16(plan._ptr, T64, f, _ptr(V), _ptr(Vbar))
+    lib.orc_encode_h16(plan._ptr, T64, _ptr(Vbar), _ptr(X))
+    lib.orc_decode_h16(plan._ptr, T64, _ptr(X), _ptr(Vbar), _ptr(D))
+    lib.orc_reduce_h16(plan._ptr, T64, f, _ptr(V), _ptr(D), _ptr(Phi))
+    return {"Vbar": Vbar, "X": X, "D": D, "Phi": Phi}
+
+
+def direct_h16(plan, T, V, fmt):
+    """eq. (1) on 16-bit inputs, fp64."""
+    sh = plan.shapes(T)
+    _check(V, np.uint16, sh["V"], "V")
+    out = np.empty(sh["Phi"], dtype=np.float64)
+    _load().orc_direct_h16(plan._ptr, C.c_int64(T), H16_FORMATS[fmt], _ptr(V), _ptr(out))
+    return out

@@ -5,6 +5,10 @@ counter = (((job*Q + q)*N + n)*T + i).  uint32 payload = top 32 bits of h.
 fp32 payload = Box-Muller on two 24-bit uniforms cut from h, evaluated in fp64
 and rounded once to fp32.  Output layout [J][N][Q][T] (file-major).
 
+16-bit payloads ("bf16", "f16") are the fp32 payload rounded once more, to nearest
+even, to bfloat16 / IEEE binary16; the numpy backend hands them out as uint16
+bit patterns, the torch backend as tensors of that dtype.
+
 Two backends produce the same recipe: numpy (host) and torch (any device).
 The uint32 payload is bit-identical across backends; the fp32 payload may
 differ in the last bit between backends (log/cos implementations), so a test
@@ -29,7 +33,10 @@ def _mix64_np(z):
 
 
 def generate_numpy(J, N, Q, T, seed, mode, sigma=1.0):
-    """Host arrays: float32 (mode "f32") or uint32 (mode "u32"), shape (J, N, Q, T)."""
+    """Host arrays: float32 (mode "f32"), uint32 (mode "u32") or uint16 bit patterns
+    (modes "bf16", "f16"), shape (J, N, Q, T)."""
+    if mode in ("bf16", "f16"):
+        return to_half_bits(generate_numpy(J, N, Q, T, seed, "f32", sigma), mode)
     out = np.empty((J, N, Q, T), dtype=np.float32 if mode == "f32" else np.uint32)
     i = np.arange(T, dtype=np.uint64)[None, :]
     q = np.arange(Q, dtype=np.uint64)[:, None]
@@ -48,6 +55,25 @@ def generate_numpy(J, N, Q, T, seed, mode, sigma=1.0):
     return out
 
 
+def to_half_bits(values, mode):
+    """uint16 patterns of float32 values rounded to nearest even: "f16" through
+    numpy's float16, "bf16" by rounding away the low 16 bits of the fp32 pattern."""
+    values = np.ascontiguousarray(values, dtype=np.float32)
+    if mode == "f16":
+        with np.errstate(over="ignore"):
+            return values.astype(np.float16).view(np.uint16)
+    b = values.view(np.uint32).astype(np.uint64)
+    return ((b + np.uint64(0x7FFF) + ((b >> np.uint64(16)) & np.uint64(1))) >> np.uint64(16)).astype(np.uint16)
+
+
+def half_bits_to_float(bits, mode):
+    """Exact float32 values of uint16 patterns."""
+    bits = np.ascontiguousarray(bits, dtype=np.uint16)
+    if mode == "f16":
+        return bits.view(np.float16).astype(np.float32)
+    return (bits.astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
 def _s64(x):
     """Two's-complement reinterpretation of an unsigned 64-bit constant."""
     x &= _MASK64
@@ -58,8 +84,11 @@ def generate_torch(J, N, Q, T, seed, mode, sigma=1.0, device="cpu"):
     """Same recipe with torch ops (int64 arithmetic wraps mod 2^64).
 
     Returns float32 for "f32"; for "u32" returns an int32 tensor holding the
-    uint32 bit patterns (torch has no arithmetic uint32 type)."""
+    uint32 bit patterns (torch has no arithmetic uint32 type); bfloat16 / float16
+    tensors for "bf16" / "f16"."""
     import torch
+
+    half = {"bf16": torch.bfloat16, "f16": torch.float16}.get(mode)
 
     def lsr(z, s):
         return (z >> s) & ((1 << (64 - s)) - 1)
@@ -69,7 +98,7 @@ def generate_torch(J, N, Q, T, seed, mode, sigma=1.0, device="cpu"):
         z = (z ^ lsr(z, 27)) * _s64(_M2)
         return z ^ lsr(z, 31)
 
-    out = torch.empty((J, N, Q, T), dtype=torch.float32 if mode == "f32" else torch.int32, device=device)
+    out = torch.empty((J, N, Q, T), dtype=half or (torch.float32 if mode == "f32" else torch.int32), device=device)
     i = torch.arange(T, dtype=torch.int64, device=device)[None, :]
     q = torch.arange(Q, dtype=torch.int64, device=device)[:, None]
     q = q[None]                                       # (1, Q, 1)
@@ -86,5 +115,6 @@ def generate_torch(J, N, Q, T, seed, mode, sigma=1.0, device="cpu"):
                 u1 = (lsr(h, 40).to(torch.float64) + 1.0) / 16777216.0
                 u2 = (lsr(h, 16) & 0xFFFFFF).to(torch.float64) / 16777216.0
                 z = sigma * torch.sqrt(-2.0 * torch.log(u1)) * torch.cos(2.0 * math.pi * u2)
-                out[j, n0:n0 + step] = z.to(torch.float32)
+                z = z.to(torch.float32)
+                out[j, n0:n0 + step] = z.to(half) if half else z
     return out
