@@ -27,8 +27,11 @@
  *
  * Payload modes: CCDC_F32_SUM (fp32, real + to combine/encode/reduce, real -
  * to decode), CCDC_U32_XOR (uint32 words of the paper's field F_{2^T},
- * + and - are both XOR; bit-exact) and CCDC_F32_SUM_XOR (fp32 values summed,
- * packets XOR-coded as bit patterns; decoding is bit-exact).
+ * + and - are both XOR; bit-exact), CCDC_F32_SUM_XOR (fp32 values summed,
+ * packets XOR-coded as bit patterns; decoding is bit-exact) and the same hybrid
+ * for 2-byte elements, CCDC_BF16_SUM_XOR / CCDC_F16_SUM_XOR.  Every buffer of a
+ * call holds elements of the bound mode's size (4 or 2 bytes) and must be
+ * aligned to it; wider alignment (16 bytes) selects the wide kernels.
  *
  * Every function returns CCDC_OK (0) or a negative ccdc_status; nothing is
  * written to an output on error and the library never aborts or throws.
@@ -61,10 +64,14 @@ enum ccdc_status {
 enum ccdc_mode {
     CCDC_F32_SUM = 0,       /* fp32: + to combine, encode, reduce; - to decode */
     CCDC_U32_XOR = 1,       /* uint32 words of F_{2^T}: XOR everywhere, bit-exact */
-    CCDC_F32_SUM_XOR = 2    /* fp32 values summed when pre-combining (files ascending) and in the
+    CCDC_F32_SUM_XOR = 2,   /* fp32 values summed when pre-combining (files ascending) and in the
                                final reduction, packets coded and decoded by XOR of their 32-bit
                                patterns, as Sec. II narrates the scheme: X holds bit patterns and
                                D equals Vbar bit for bit */
+    CCDC_BF16_SUM_XOR = 3,  /* the same hybrid on bfloat16 bit patterns (2-byte elements): sums are
+                               carried in fp32 and rounded once, to nearest even, when a packet or an
+                               output is stored; X holds XORs of 16-bit patterns */
+    CCDC_F16_SUM_XOR = 4    /* the same on IEEE binary16 bit patterns */
 };
 
 /* Items for ccdc_plan_query.  Scalars are written as one int64_t; tables as
@@ -132,7 +139,8 @@ void ccdc_plan_destroy(ccdc_plan_t *plan);   /* frees host and device parts; NUL
  * Fix the value length T (elements) and the payload mode: computes W, the
  * segment split (Sec. IV-B) and the traffic the schedule puts on the wire.
  * Host only.  May be called again; that drops any device tables.
- * Errors: CCDC_EINVAL (T<1, unknown mode), CCDC_ESIZE when a buffer would
+ * Errors: CCDC_EINVAL (T<1, unknown mode, a hybrid mode on a plan of
+ * ccdc_plan_compression, which codes nothing), CCDC_ESIZE when a buffer would
  * hold more than 2^40 elements or a kernel's work-item count would pass 2^31-1.
  */
 int ccdc_plan_bind(ccdc_plan_t *plan, int64_t T, int mode);

@@ -15,8 +15,9 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libccdc.so")
 
 OK, EINVAL, ENOMEM, EHIP, ESIZE, ESTATE = 0, -1, -2, -3, -4, -5
-F32_SUM, U32_XOR, F32_SUM_XOR = 0, 1, 2
-MODES = {"f32": F32_SUM, "u32": U32_XOR, "h32": F32_SUM_XOR}
+F32_SUM, U32_XOR, F32_SUM_XOR, BF16_SUM_XOR, F16_SUM_XOR = 0, 1, 2, 3, 4
+MODES = {"f32": F32_SUM, "u32": U32_XOR, "h32": F32_SUM_XOR, "bf16": BF16_SUM_XOR, "f16": F16_SUM_XOR}
+ELEM_BYTES = {F32_SUM: 4, U32_XOR: 4, F32_SUM_XOR: 4, BF16_SUM_XOR: 2, F16_SUM_XOR: 2}
 
 # enum ccdc_query
 (Q_K, Q_R, Q_Q, Q_N, Q_J, Q_C, Q_M, Q_NBATCH, Q_NROUND, Q_T, Q_MODE, Q_W, Q_SEG_LEN,
@@ -90,12 +91,12 @@ def _check(status, where):
         raise CcdcError(status, where)
 
 
-def _dev_ptr(t, name):
+def _dev_ptr(t, name, elem_bytes=4):
     """Device address of a contiguous CUDA/HIP torch tensor."""
     if not t.is_cuda or not t.is_contiguous():
         raise ValueError(f"{name}: need a contiguous device tensor")
-    if t.element_size() != 4:
-        raise ValueError(f"{name}: need 4-byte elements, got {t.dtype}")
+    if t.element_size() != elem_bytes:
+        raise ValueError(f"{name}: need {elem_bytes}-byte elements, got {t.dtype}")
     return C.c_void_p(t.data_ptr())
 
 
@@ -132,8 +133,10 @@ class Plan:
 
     # ---- plan construction
     def bind(self, T, mode):
-        _check(self._lib.ccdc_plan_bind(self._h, int(T), MODES.get(mode, mode)), "ccdc_plan_bind")
+        mode = MODES.get(mode, mode)
+        _check(self._lib.ccdc_plan_bind(self._h, int(T), mode), "ccdc_plan_bind")
         self._shapes = None
+        self._elem_bytes = ELEM_BYTES[mode]
         return self
 
     def upload(self):
@@ -225,7 +228,7 @@ class Plan:
         want = self._numel[key]
         if t.numel() != want:
             raise ValueError(f"{name}: need {want} elements, got {t.numel()}")
-        return _dev_ptr(t, name)
+        return _dev_ptr(t, name, self._elem_bytes)
 
     # ---- stages (asynchronous on `stream`, default torch's current stream)
     def combine(self, V, Vbar, stream=None):

@@ -1,8 +1,8 @@
 // HIP kernels (gfx950) and the C entry points of libccdc.
 //
 // Everything here is a streaming, bandwidth-bound elementwise pass: every
-// work item moves one pack (16 bytes when T is a multiple of 4, else one
-// element) per operand, consecutive lanes touch consecutive packs of the same
+// work item moves one pack (16 bytes when the value length allows it, else 8
+// bytes or one element) per operand, consecutive lanes touch consecutive packs of the same
 // row, and there is no reuse across work items, so no LDS tiling and no MFMA.
 #include <new>
 
@@ -29,9 +29,9 @@ __global__ __launch_bounds__(kBlock) void k_combine(const typename A::elem *__re
     const uint32_t row = idx / Wv, e = idx - row * Wv;
     const typename A::elem *src = V + src_off[row] + (int64_t)e * VEC;
     const int files = row_files ? row_files[row] : m;
-    P acc = load_stream<P>(src);
-    for (int f = 1; f < files; f++) acc = O::add(acc, load_stream<P>(src + f * file_stride));
-    reinterpret_cast<P *>(Vbar)[idx] = acc;
+    typename O::Q acc = O::widen(load_stream<P>(src));
+    for (int f = 1; f < files; f++) acc = O::accum(acc, load_stream<P>(src + f * file_stride));
+    reinterpret_cast<P *>(Vbar)[idx] = O::narrow(acc);
 }
 
 // Pre-combining for short packets and long batches (few packs per packet, many
@@ -40,7 +40,8 @@ __global__ __launch_bounds__(kBlock) void k_combine(const typename A::elem *__re
 // adds files g, g+G, g+2G, ... (G = 64/SEG) of the batch, each lane one pack, and
 // the G segment sums are then added across the wavefront by a butterfly of lane
 // exchanges.  The order of additions is fixed by (m, SEG), not by timing; it
-// differs from k_combine's file order, so the bit-exact h32 mode does not use it.
+// differs from k_combine's file order, so the algebras whose packets are coded
+// bit patterns (fixed_order) do not use it.
 template <class A, int VEC>
 __global__ __launch_bounds__(64) void k_combine_wave(const typename A::elem *__restrict__ V,
                                                      typename A::elem *__restrict__ Vbar,
@@ -55,13 +56,13 @@ __global__ __launch_bounds__(64) void k_combine_wave(const typename A::elem *__r
     const int lane = threadIdx.x;
     const int e = lane % seg, g = lane / seg, G = 64 / seg;
     const E *src = V + src_off[row] + (int64_t)e * VEC;
-    P acc = O::zero();
+    typename O::Q acc = O::azero();
     if ((uint32_t)e < Wv)
-        for (int f = g; f < m; f += G) acc = O::add(acc, load_stream<P>(src + f * file_stride));
+        for (int f = g; f < m; f += G) acc = O::accum(acc, load_stream<P>(src + f * file_stride));
     // segmented butterfly: after the step with distance d, lane l holds the sum of
     // the segments whose index differs from its own only in the bits below d/seg
     for (int d = seg; d < 64; d <<= 1) {
-        P other;
+        typename O::Q other;
 #pragma unroll
         for (int i = 0; i < VEC; i++) {
             uint32_t bits;
@@ -72,7 +73,7 @@ __global__ __launch_bounds__(64) void k_combine_wave(const typename A::elem *__r
         // lower segment first on both sides so that every lane adds in the same order
         acc = (lane & d) ? O::add(other, acc) : O::add(acc, other);
     }
-    if (g == 0 && (uint32_t)e < Wv) reinterpret_cast<P *>(Vbar)[(size_t)row * Wv + e] = acc;
+    if (g == 0 && (uint32_t)e < Wv) reinterpret_cast<P *>(Vbar)[(size_t)row * Wv + e] = O::narrow(acc);
 }
 
 // ------------------------------------------------------------------- encode
@@ -161,9 +162,9 @@ __global__ __launch_bounds__(kBlock) void k_shuffle_fused(const typename A::elem
         const uint32_t pos = label_rank(a, b) * Lv + x;
         if (pos >= Wv) return O::zero();
         const typename A::elem *s = V + src[b] + (int64_t)pos * VEC;
-        P acc = load_stream<P>(s);
-        for (int f = 1; f < m; f++) acc = O::add(acc, load_stream<P>(s + f * file_stride));
-        return acc;
+        typename O::Q acc = O::widen(load_stream<P>(s));
+        for (int f = 1; f < m; f++) acc = O::accum(acc, load_stream<P>(s + f * file_stride));
+        return O::narrow(acc);
     };
 
     P *Drows = reinterpret_cast<P *>(D) + (size_t)u * r1 * Wv;
@@ -210,11 +211,12 @@ __global__ __launch_bounds__(kBlock) void k_shuffle_fused(const typename A::elem
 // c functions of one job) is the sum of a list of W-long rows, some in V (files
 // the node stores), some in D (packets it decoded).  The list is cut into
 // `split` chunks; work item = (o, chunk, pack).  With split > 1 the chunk sums
-// go to the workspace and k_reduce_final adds them in chunk order.
+// go, not yet narrowed, to the workspace and k_reduce_final adds them in chunk order.
 template <class A, int VEC>
 __global__ __launch_bounds__(kBlock) void k_reduce_rows(const typename A::elem *__restrict__ V,
                                                         const typename A::elem *__restrict__ D,
                                                         typename A::elem *__restrict__ out,
+                                                        typename A::acc *__restrict__ part,
                                                         const int64_t *__restrict__ red_ptr,
                                                         const int64_t *__restrict__ red_row,
                                                         const int64_t *__restrict__ red_out, uint32_t Wv,
@@ -230,14 +232,15 @@ __global__ __launch_bounds__(kBlock) void k_reduce_rows(const typename A::elem *
     if (e >= Wv) return;
     const int64_t first = red_ptr[o], n = red_ptr[o + 1] - first;
     const int64_t lo = first + n * s / split, hi = first + n * (s + 1) / split;
-    P acc = O::zero();
+    typename O::Q acc = O::azero();
 #pragma unroll 4
     for (int64_t i = lo; i < hi; i++) {
         const int64_t row = red_row[i];
         const typename A::elem *base = (row & 1) ? D : V;
-        acc = O::add(acc, load_stream<P>(reinterpret_cast<const P *>(base + (row >> 1)) + e));
+        acc = O::accum(acc, load_stream<P>(reinterpret_cast<const P *>(base + (row >> 1)) + e));
     }
-    reinterpret_cast<P *>(out + (int64_t)s * chunk_stride + red_out[o])[e] = acc;
+    if (split > 1) reinterpret_cast<typename O::Q *>(part + (int64_t)s * chunk_stride + red_out[o])[e] = acc;
+    else reinterpret_cast<P *>(out + red_out[o])[e] = O::narrow(acc);
 }
 
 void release_device(ccdc_plan_t *p)
@@ -292,13 +295,15 @@ int run_combine(const ccdc_plan_t *p, const void *V, void *Vbar, hipStream_t st)
 #ifndef CCDC_COMBINE_WAVE_MIN_FILES
 #define CCDC_COMBINE_WAVE_MIN_FILES 8
 #endif
-    if (Wv <= 16 && p->m >= CCDC_COMBINE_WAVE_MIN_FILES && p->mode != CCDC_F32_SUM_XOR && !p->d_row_files) {
-        int seg = 1;
-        while ((uint32_t)seg < Wv) seg <<= 1;
-        const uint32_t rows = (uint32_t)p->nrows;
-        k_combine_wave<A, VEC><<<rows, 64, 0, st>>>((const E *)V, (E *)Vbar, p->d_src_off, Wv, seg, p->m,
-                                                    (int64_t)p->Q * p->T, rows);
-        return launched();
+    if constexpr (!A::fixed_order) {
+        if (Wv <= 16 && p->m >= CCDC_COMBINE_WAVE_MIN_FILES && !p->d_row_files) {
+            int seg = 1;
+            while ((uint32_t)seg < Wv) seg <<= 1;
+            const uint32_t rows = (uint32_t)p->nrows;
+            k_combine_wave<A, VEC><<<rows, 64, 0, st>>>((const E *)V, (E *)Vbar, p->d_src_off, Wv, seg, p->m,
+                                                        (int64_t)p->Q * p->T, rows);
+            return launched();
+        }
     }
     k_combine<A, VEC><<<cdiv(items, kBlock), kBlock, 0, st>>>((const E *)V, (E *)Vbar, p->d_src_off, p->d_row_files,
                                                                Wv, p->m, (int64_t)p->Q * p->T, (uint32_t)items);
@@ -362,15 +367,15 @@ int run_reduce(const ccdc_plan_t *p, const void *V, const void *D, void *Phi, hi
     const int split = p->red_split;
     const uint64_t blocks = (uint64_t)p->nout * split * tiles;
     const int64_t chunk_stride = (int64_t)p->J * p->Q * p->T;
-    E *out = split > 1 ? (E *)p->d_workspace : (E *)Phi;
-    k_reduce_rows<A, VEC><<<(uint32_t)blocks, kBlock, 0, st>>>((const E *)V, (const E *)D, out, p->d_red_ptr,
-                                                                p->d_red_row, p->d_red_out, Wv, tiles, split,
-                                                                chunk_stride);
+    using Acc = typename A::acc;
+    k_reduce_rows<A, VEC><<<(uint32_t)blocks, kBlock, 0, st>>>((const E *)V, (const E *)D, (E *)Phi,
+                                                                (Acc *)p->d_workspace, p->d_red_ptr, p->d_red_row,
+                                                                p->d_red_out, Wv, tiles, split, chunk_stride);
     int rc = launched();
     if (rc != CCDC_OK || split == 1) return rc;
     const uint64_t items = (uint64_t)chunk_stride / VEC;
     const int G = reduce_final_groups((int64_t)items, split);
-    k_reduce_final<A, VEC><<<cdiv(items, kBlock / G), kBlock, 0, st>>>((const E *)p->d_workspace, (E *)Phi, split,
+    k_reduce_final<A, VEC><<<cdiv(items, kBlock / G), kBlock, 0, st>>>((const Acc *)p->d_workspace, (E *)Phi, split,
                                                                         chunk_stride / VEC, (uint32_t)items, G);
     return launched();
 }
@@ -385,6 +390,18 @@ int run_reduce(const ccdc_plan_t *p, const void *V, const void *D, void *Phi, hi
             return CALL;                                              \
         } else if ((p)->mode == CCDC_F32_SUM_XOR) {                   \
             using A = HybF32;                                         \
+            if ((vec) == 4) { constexpr int VEC = 4; return CALL; }   \
+            constexpr int VEC = 1;                                    \
+            return CALL;                                              \
+        } else if ((p)->mode == CCDC_BF16_SUM_XOR) {                  \
+            using A = HybBF16;                                        \
+            if ((vec) == 8) { constexpr int VEC = 8; return CALL; }   \
+            if ((vec) == 4) { constexpr int VEC = 4; return CALL; }   \
+            constexpr int VEC = 1;                                    \
+            return CALL;                                              \
+        } else if ((p)->mode == CCDC_F16_SUM_XOR) {                   \
+            using A = HybF16;                                         \
+            if ((vec) == 8) { constexpr int VEC = 8; return CALL; }   \
             if ((vec) == 4) { constexpr int VEC = 4; return CALL; }   \
             constexpr int VEC = 1;                                    \
             return CALL;                                              \

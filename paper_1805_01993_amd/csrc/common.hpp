@@ -11,32 +11,92 @@
 namespace ccdc {
 
 // ----------------------------------------------------------------- algebras
-// add: pre-combining and the final reduction.  code / uncode: forming a coded
-// packet and cancelling side information from it.
+// elem: what V, Vbar, X, D and Phi hold.  acc: what sums are carried in.
+// widen / add / narrow: pre-combining and the final reduction (a sum is
+// narrowed once, when it is stored as an elem).  code / uncode: forming a coded
+// packet and cancelling side information from it.  fixed_order: the bits of a
+// pre-combined packet are part of the result (they are XOR-coded), so every
+// kernel adds a batch's files in ascending order.
 struct SumF32 {                       // real numbers throughout
     using elem = float;
+    using acc = float;
+    static constexpr bool fixed_order = false;
     static __device__ __forceinline__ elem zero() { return 0.0f; }
-    static __device__ __forceinline__ elem add(elem a, elem b) { return a + b; }
+    static __device__ __forceinline__ acc azero() { return 0.0f; }
+    static __device__ __forceinline__ acc widen(elem a) { return a; }
+    static __device__ __forceinline__ elem narrow(acc a) { return a; }
+    static __device__ __forceinline__ acc add(acc a, acc b) { return a + b; }
     static __device__ __forceinline__ elem code(elem a, elem b) { return a + b; }
     static __device__ __forceinline__ elem uncode(elem a, elem b) { return a - b; }
 };
 struct XorU32 {                       // the field F_{2^T} throughout
     using elem = uint32_t;
+    using acc = uint32_t;
+    static constexpr bool fixed_order = false;
     static __device__ __forceinline__ elem zero() { return 0u; }
-    static __device__ __forceinline__ elem add(elem a, elem b) { return a ^ b; }
+    static __device__ __forceinline__ acc azero() { return 0u; }
+    static __device__ __forceinline__ acc widen(elem a) { return a; }
+    static __device__ __forceinline__ elem narrow(acc a) { return a; }
+    static __device__ __forceinline__ acc add(acc a, acc b) { return a ^ b; }
     static __device__ __forceinline__ elem code(elem a, elem b) { return a ^ b; }
     static __device__ __forceinline__ elem uncode(elem a, elem b) { return a ^ b; }
 };
 struct HybF32 {                       // numbers are summed, packets are XOR-coded bit patterns (Sec. II)
     using elem = float;
+    using acc = float;
+    static constexpr bool fixed_order = true;
     static __device__ __forceinline__ elem zero() { return 0.0f; }    // all-zero bits: also the XOR identity
-    static __device__ __forceinline__ elem add(elem a, elem b) { return a + b; }
+    static __device__ __forceinline__ acc azero() { return 0.0f; }
+    static __device__ __forceinline__ acc widen(elem a) { return a; }
+    static __device__ __forceinline__ elem narrow(acc a) { return a; }
+    static __device__ __forceinline__ acc add(acc a, acc b) { return a + b; }
     static __device__ __forceinline__ elem code(elem a, elem b)
     {
         return __uint_as_float(__float_as_uint(a) ^ __float_as_uint(b));
     }
     static __device__ __forceinline__ elem uncode(elem a, elem b) { return code(a, b); }
 };
+// The same hybrid for 16-bit floating-point payloads: elements are bit patterns
+// of bfloat16 (BF) or IEEE binary16 numbers, sums are carried in fp32 and
+// rounded once, to nearest even, when stored.
+template <bool BF>
+struct Hyb16 {
+    using elem = uint16_t;
+    using acc = float;
+    static constexpr bool fixed_order = true;
+    static __device__ __forceinline__ elem zero() { return 0; }
+    static __device__ __forceinline__ acc azero() { return 0.0f; }
+    static __device__ __forceinline__ acc widen(elem a)
+    {
+        if constexpr (BF) {
+            return __uint_as_float((uint32_t)a << 16);
+        } else {
+            _Float16 h;
+            __builtin_memcpy(&h, &a, 2);
+            return (float)h;
+        }
+    }
+    static __device__ __forceinline__ elem narrow(acc a)
+    {
+        if constexpr (BF) {
+            const uint32_t b = __float_as_uint(a);
+            if (a != a) return (elem)((b >> 16) | 0x7FC0u);
+            // drop 16 fraction bits: add half of the dropped range, one less when the
+            // kept part is even; a carry runs into the exponent (up to infinity)
+            return (elem)((b + 0x7FFFu + ((b >> 16) & 1u)) >> 16);
+        } else {
+            const _Float16 h = (_Float16)a;              // the hardware conversion rounds to nearest even
+            elem out;
+            __builtin_memcpy(&out, &h, 2);
+            return out;
+        }
+    }
+    static __device__ __forceinline__ acc add(acc a, acc b) { return a + b; }
+    static __device__ __forceinline__ elem code(elem a, elem b) { return (elem)(a ^ b); }
+    static __device__ __forceinline__ elem uncode(elem a, elem b) { return (elem)(a ^ b); }
+};
+using HybBF16 = Hyb16<true>;
+using HybF16 = Hyb16<false>;
 
 // VEC consecutive elements moved by one load/store.
 template <class E, int VEC>
@@ -46,7 +106,8 @@ struct alignas(sizeof(E) * VEC) Pack {
 
 template <class A, int VEC>
 struct Ops {
-    using P = Pack<typename A::elem, VEC>;
+    using P = Pack<typename A::elem, VEC>;       // as stored
+    using Q = Pack<typename A::acc, VEC>;        // as summed
     static __device__ __forceinline__ P zero()
     {
         P z;
@@ -54,12 +115,34 @@ struct Ops {
         for (int i = 0; i < VEC; i++) z.v[i] = A::zero();
         return z;
     }
-    static __device__ __forceinline__ P add(P a, P b)
+    static __device__ __forceinline__ Q azero()
+    {
+        Q z;
+#pragma unroll
+        for (int i = 0; i < VEC; i++) z.v[i] = A::azero();
+        return z;
+    }
+    static __device__ __forceinline__ Q widen(P a)
+    {
+        Q q;
+#pragma unroll
+        for (int i = 0; i < VEC; i++) q.v[i] = A::widen(a.v[i]);
+        return q;
+    }
+    static __device__ __forceinline__ P narrow(Q a)
+    {
+        P p;
+#pragma unroll
+        for (int i = 0; i < VEC; i++) p.v[i] = A::narrow(a.v[i]);
+        return p;
+    }
+    static __device__ __forceinline__ Q add(Q a, Q b)
     {
 #pragma unroll
         for (int i = 0; i < VEC; i++) a.v[i] = A::add(a.v[i], b.v[i]);
         return a;
     }
+    static __device__ __forceinline__ Q accum(Q a, P b) { return add(a, widen(b)); }
     static __device__ __forceinline__ P code(P a, P b)
     {
 #pragma unroll
@@ -85,19 +168,23 @@ struct Ops {
 #ifndef CCDC_STREAMING_HINTS
 #define CCDC_STREAMING_HINTS 1
 #endif
-template <int VEC>
-struct Bits {
-    typedef uint32_t type __attribute__((ext_vector_type(VEC)));
+template <int BYTES>
+struct Bits {                                       // 8 or 16 bytes: a vector of 32-bit words
+    typedef uint32_t type __attribute__((ext_vector_type(BYTES / 4)));
 };
 template <>
-struct Bits<1> {
+struct Bits<4> {
     typedef uint32_t type;
+};
+template <>
+struct Bits<2> {
+    typedef uint16_t type;
 };
 template <class P>
 __device__ __forceinline__ P load_stream(const void *p)
 {
 #if CCDC_STREAMING_HINTS
-    using B = typename Bits<sizeof(P) / 4>::type;
+    using B = typename Bits<sizeof(P)>::type;
     const B b = __builtin_nontemporal_load(reinterpret_cast<const B *>(p));
     P out;
     __builtin_memcpy(&out, &b, sizeof(P));
@@ -110,7 +197,7 @@ template <class P>
 __device__ __forceinline__ void store_stream(void *p, const P &v)
 {
 #if CCDC_STREAMING_HINTS
-    using B = typename Bits<sizeof(P) / 4>::type;
+    using B = typename Bits<sizeof(P)>::type;
     B b;
     __builtin_memcpy(&b, &v, sizeof(P));
     __builtin_nontemporal_store(b, reinterpret_cast<B *>(p));
@@ -128,19 +215,20 @@ __device__ __forceinline__ int label_rank(int a, int b) { return a - (a > b ? 1 
 // every G-th chunk (g, g+G, ...), then the G group sums are added in group
 // order.  The order is fixed by (split, G), so results repeat run to run.
 template <class A, int VEC>
-__global__ __launch_bounds__(kBlock) void k_reduce_final(const typename A::elem *__restrict__ part,
+__global__ __launch_bounds__(kBlock) void k_reduce_final(const typename A::acc *__restrict__ part,
                                                          typename A::elem *__restrict__ Phi, int split,
                                                          int64_t chunk_packs, uint32_t items, int G)
 {
     using O = Ops<A, VEC>;
     using P = typename O::P;
-    __shared__ P sums[kBlock];
+    using Q = typename O::Q;
+    __shared__ Q sums[kBlock];
     const int per_block = kBlock / G;                    // packs of this workgroup
     const int e = threadIdx.x % per_block, g = threadIdx.x / per_block;
     const uint32_t idx = blockIdx.x * per_block + e;
-    P acc = O::zero();
+    Q acc = O::azero();
     if (idx < items) {
-        const P *src = reinterpret_cast<const P *>(part) + idx;
+        const Q *src = reinterpret_cast<const Q *>(part) + idx;
 #pragma unroll 4
         for (int s = g; s < split; s += G) acc = O::add(acc, src[(int64_t)s * chunk_packs]);
     }
@@ -148,7 +236,7 @@ __global__ __launch_bounds__(kBlock) void k_reduce_final(const typename A::elem 
     __syncthreads();
     if (g == 0 && idx < items) {
         for (int k = 1; k < G; k++) acc = O::add(acc, sums[k * per_block + e]);
-        reinterpret_cast<P *>(Phi)[idx] = acc;
+        reinterpret_cast<P *>(Phi)[idx] = O::narrow(acc);
     }
 }
 
@@ -174,18 +262,30 @@ inline int ready(const ccdc_plan_t *p)
     return CCDC_OK;
 }
 
-// Pack width for this call: 4 when the value length and every pointer allow it.
+inline int elem_bytes(int mode) { return (mode == CCDC_BF16_SUM_XOR || mode == CCDC_F16_SUM_XOR) ? 2 : 4; }
+
+// Pack width (elements) for this call: 16 bytes when the value length, the
+// segment length and every pointer allow it; for 2-byte elements else 8 bytes;
+// else one element.
 template <class... Ptr>
 int pick_vec(const ccdc_plan_t *p, int *vec, Ptr... ptrs)
 {
     const void *list[] = {ptrs...};
-    bool a16 = true;
+    const size_t eb = (size_t)elem_bytes(p->mode);
+    bool a16 = true, a8 = true;
     for (const void *q : list) {
         if (!q) return CCDC_EINVAL;
-        if (!aligned(q, 4)) return CCDC_EINVAL;
+        if (!aligned(q, eb)) return CCDC_EINVAL;
         a16 = a16 && aligned(q, 16);
+        a8 = a8 && aligned(q, 8);
     }
-    *vec = (p->T % 4 == 0 && a16) ? 4 : 1;
+    if (eb == 4) {
+        *vec = (p->T % 4 == 0 && a16) ? 4 : 1;
+    } else {
+        if (p->T % 8 == 0 && p->ell % 8 == 0 && a16) *vec = 8;
+        else if (p->T % 4 == 0 && a8) *vec = 4;
+        else *vec = 1;
+    }
     return CCDC_OK;
 }
 

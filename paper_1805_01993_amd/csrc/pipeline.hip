@@ -17,7 +17,8 @@ using namespace ccdc;
 // this read-add-write of the round's slots.)
 // The files a node stores itself are added from V the same way.  With more than
 // one chunk the per-chunk outputs go to the workspace and k_reduce_final adds
-// them in chunk order.
+// them in chunk order.  Running outputs and chunk outputs are sums in the making
+// (the algebra's acc type); they are narrowed to elements once, when Phi is written.
 //
 // LDS capacity, not registers, bounds how many wavefronts fit on a compute
 // unit, so the loads of the next PF rounds are kept in flight in registers
@@ -46,20 +47,21 @@ constexpr int prefetch_depth()
 
 template <class A, int VEC, int R1, bool MULTI, bool RAGGED>
 __global__ __launch_bounds__(ccdc::kPipeLanes) void k_pipeline(
-    const typename A::elem *__restrict__ V, typename A::elem *__restrict__ X, typename A::elem *__restrict__ out,
-    const int64_t *__restrict__ src_off, const int32_t *__restrict__ member, const int64_t *__restrict__ loc_row,
+    const typename A::elem *__restrict__ V, typename A::elem *__restrict__ X, typename A::elem *__restrict__ Phi,
+    typename A::acc *__restrict__ part, const int64_t *__restrict__ src_off, const int32_t *__restrict__ member, const int64_t *__restrict__ loc_row,
     int K, uint32_t Lv, uint32_t Wv, int m, int64_t file_stride, uint32_t R, uint32_t tiles, uint32_t chunks,
     uint32_t n_loc, int64_t chunk_stride)
 {
     using E = typename A::elem;
     using O = Ops<A, VEC>;
     using P = typename O::P;
+    using Q = typename O::Q;
     constexpr int r = R1 - 1;
     constexpr int LANES = ccdc::kPipeLanes;
     constexpr int PF = MULTI ? 1 : prefetch_depth<VEC, R1>();
     constexpr int PFL = PF * R1;                     // own-file rows in flight (r packs each)
     extern __shared__ __align__(16) unsigned char smem[];
-    P *acc = reinterpret_cast<P *>(smem) + threadIdx.x;      // slot i of this lane: acc[i * LANES]
+    Q *acc = reinterpret_cast<Q *>(smem) + threadIdx.x;      // slot i of this lane: acc[i * LANES]
 
     // Workgroups are handed to the 8 XCDs round-robin.  Renumber them so that each
     // XCD gets a contiguous range of (chunk, tile) pairs: the tiles of one chunk
@@ -84,7 +86,7 @@ __global__ __launch_bounds__(ccdc::kPipeLanes) void k_pipeline(
     auto pack_at = [](const E *row, uint32_t byte_off) -> P {
         return load_stream<P>(reinterpret_cast<const char *>(row) + byte_off);
     };
-    for (int i = 0; i < K * r; i++) acc[i * LANES] = O::zero();
+    for (int i = 0; i < K * r; i++) acc[i * LANES] = O::azero();
 
     struct Row {                      // one round's table entries (wave-uniform)
         int64_t src[R1];              // element offset in V of packet b's first file
@@ -111,8 +113,11 @@ __global__ __launch_bounds__(ccdc::kPipeLanes) void k_pipeline(
 #pragma unroll
             for (int rho = 0; rho < r; rho++) {
                 P v = pack_at(row, offb[rho]);
-                if constexpr (MULTI)
-                    for (int f = 1; f < m; f++) v = O::add(v, pack_at(row + f * file_stride, offb[rho]));
+                if constexpr (MULTI) {
+                    Q sum = O::widen(v);
+                    for (int f = 1; f < m; f++) sum = O::accum(sum, pack_at(row + f * file_stride, offb[rho]));
+                    v = O::narrow(sum);
+                }
                 if constexpr (RAGGED) v = O::select(valid[rho], v, O::zero());
                 s.w[b][rho] = v;
             }
@@ -122,7 +127,7 @@ __global__ __launch_bounds__(ccdc::kPipeLanes) void k_pipeline(
     // The r(r+1) slots of a round are distinct (receiver b, segment rank(a,b)), so
     // they are read together, updated, and written together: one LDS wait a round.
     auto consume = [&](uint32_t u, const Stage &s) {
-        P cur[R1][r];                 // cur[b][rho]: running output of node s_b, segment rho
+        Q cur[R1][r];                 // cur[b][rho]: running output of node s_b, segment rho
 #pragma unroll
         for (int b = 0; b < R1; b++)
 #pragma unroll
@@ -143,7 +148,7 @@ __global__ __launch_bounds__(ccdc::kPipeLanes) void k_pipeline(
                 for (int b2 = 0; b2 < R1; b2++)
                     if (b2 != a && b2 != b) d = O::uncode(d, s.w[b2][a - (a > b2 ? 1 : 0)]);
                 // a slot past a short segment collects zeros and is never written out
-                cur[b][rho] = O::add(cur[b][rho], d);
+                cur[b][rho] = O::accum(cur[b][rho], d);
             }
         }
 #pragma unroll
@@ -199,11 +204,11 @@ __global__ __launch_bounds__(ccdc::kPipeLanes) void k_pipeline(
         }
     };
     auto consume_own = [&](const Own &s) {
-        P cur[r];
+        Q cur[r];
 #pragma unroll
         for (int rho = 0; rho < r; rho++) cur[rho] = acc[(s.k * r + rho) * LANES];
 #pragma unroll
-        for (int rho = 0; rho < r; rho++) acc[(s.k * r + rho) * LANES] = O::add(cur[rho], s.w[rho]);
+        for (int rho = 0; rho < r; rho++) acc[(s.k * r + rho) * LANES] = O::accum(cur[rho], s.w[rho]);
     };
     const uint32_t i0 = (uint32_t)((uint64_t)n_loc * chunk / chunks);
     const uint32_t i1 = (uint32_t)((uint64_t)n_loc * (chunk + 1) / chunks);
@@ -227,14 +232,18 @@ __global__ __launch_bounds__(ccdc::kPipeLanes) void k_pipeline(
             if (full * PFL + s < nl) consume_own(ow[s]);
     }
 
-    // write the chunk's outputs
-    E *dst = out + (int64_t)chunk * chunk_stride;
+    // write the chunk's outputs: the only chunk straight to Phi, else to its slice of the workspace
     const int64_t W = (int64_t)Wv * VEC;
+    typename A::acc *dst = part + (int64_t)chunk * chunk_stride;
     for (int k = 0; k < K; k++) {
 #pragma unroll
-        for (int rho = 0; rho < r; rho++)
-            if (valid[rho])
-                *reinterpret_cast<P *>(reinterpret_cast<char *>(dst + k * W) + offb[rho]) = acc[(k * r + rho) * LANES];
+        for (int rho = 0; rho < r; rho++) {
+            if (!valid[rho]) continue;
+            const int64_t pos = k * W + (int64_t)(offb[rho] / sizeof(E));        // element index in [K][W]
+            const Q v = acc[(k * r + rho) * LANES];
+            if (chunks == 1) *reinterpret_cast<P *>(Phi + pos) = O::narrow(v);
+            else *reinterpret_cast<Q *>(dst + pos) = v;
+        }
     }
 }
 
@@ -265,12 +274,12 @@ int launch_pipeline(const ccdc_plan_t *p, const void *V, void *X, void *Phi, hip
     using E = typename A::elem;
     const uint32_t Wv = (uint32_t)(p->W / VEC), Lv = (uint32_t)(p->ell / VEC);
     const uint32_t tiles = cdiv(Lv, ccdc::kPipeLanes);
-    const size_t lds = (size_t)p->K * p->r * ccdc::kPipeLanes * VEC * sizeof(E);
+    const size_t lds = (size_t)p->K * p->r * ccdc::kPipeLanes * VEC * sizeof(typename A::acc);
     auto go = [&](auto kernel) {
         const int chunks = chunks_for(p, kernel, tiles, lds);
-        void *out = chunks > 1 ? p->d_workspace : Phi;
         kernel<<<tiles * (uint32_t)chunks, ccdc::kPipeLanes, lds, st>>>(
-            (const E *)V, (E *)X, (E *)out, p->d_src_off, p->d_member, p->d_loc_row, p->K, Lv, Wv, p->m,
+            (const E *)V, (E *)X, (E *)Phi, (typename A::acc *)p->d_workspace, p->d_src_off, p->d_member, p->d_loc_row,
+            p->K, Lv, Wv, p->m,
             (int64_t)p->Q * p->T, (uint32_t)p->nround, tiles, (uint32_t)chunks,
             (uint32_t)(p->K * p->pipe_local_rows), (int64_t)p->K * p->W);
         *chunks_out = chunks;
@@ -286,6 +295,7 @@ template <class A, int VEC>
 int run_pipeline(const ccdc_plan_t *p, const void *V, void *X, void *Phi, bool wide_final, hipStream_t st)
 {
     using E = typename A::elem;
+    using Acc = typename A::acc;
     int chunks = 1, rc;
     switch (p->r + 1) {
     case 2: rc = launch_pipeline<A, VEC, 2>(p, V, X, Phi, st, &chunks); break;
@@ -299,11 +309,11 @@ int run_pipeline(const ccdc_plan_t *p, const void *V, void *X, void *Phi, bool w
     const int64_t n = (int64_t)p->K * p->W;
     if (wide_final) {
         const int G = reduce_final_groups(n / 4, chunks);
-        k_reduce_final<A, 4><<<cdiv(n / 4, kBlock / G), kBlock, 0, st>>>((const E *)p->d_workspace, (E *)Phi, chunks,
+        k_reduce_final<A, 4><<<cdiv(n / 4, kBlock / G), kBlock, 0, st>>>((const Acc *)p->d_workspace, (E *)Phi, chunks,
                                                                           n / 4, (uint32_t)(n / 4), G);
     } else {
         const int G = reduce_final_groups(n, chunks);
-        k_reduce_final<A, 1><<<cdiv(n, kBlock / G), kBlock, 0, st>>>((const E *)p->d_workspace, (E *)Phi, chunks, n,
+        k_reduce_final<A, 1><<<cdiv(n, kBlock / G), kBlock, 0, st>>>((const Acc *)p->d_workspace, (E *)Phi, chunks, n,
                                                                       (uint32_t)n, G);
     }
     return launched();
@@ -315,15 +325,17 @@ extern "C" {
 
 int ccdc_pipeline_fused(const ccdc_plan_t *plan, const void *V, void *X, void *Phi, void *stream)
 {
-    int rc = ready(plan), vec4 = 1;
+    int rc = ready(plan), vec_any = 1;
     if (rc != CCDC_OK) return rc;
     if (plan->compression) return CCDC_ESTATE;       // nothing is coded in that scheme
     if (!plan->pipe_ok) return CCDC_ESIZE;
-    if ((rc = pick_vec(plan, &vec4, V, (const void *)X, (const void *)Phi)) != CCDC_OK) return rc;
-    // widest pack allowed by the plan's LDS budget and by the pointers
+    if ((rc = pick_vec(plan, &vec_any, V, (const void *)X, (const void *)Phi)) != CCDC_OK) return rc;
+    // widest pack allowed by the plan's LDS budget (the running outputs take 4 bytes
+    // an element in every mode) and by the pointers
+    const size_t eb = (size_t)elem_bytes(plan->mode);
     int vec = plan->pipe_vec;
-    while (vec > 1 && !(aligned(V, 4 * vec) && aligned(X, 4 * vec) && aligned(Phi, 4 * vec))) vec /= 2;
-    const bool wide_final = vec4 == 4;
+    while (vec > 1 && !(aligned(V, eb * vec) && aligned(X, eb * vec) && aligned(Phi, eb * vec))) vec /= 2;
+    const bool wide_final = vec_any >= 4;            // Phi can be written four elements at a time
     hipStream_t st = (hipStream_t)stream;
     if (plan->mode == CCDC_F32_SUM) {
         if (vec == 4) return run_pipeline<SumF32, 4>(plan, V, X, Phi, wide_final, st);
@@ -334,6 +346,16 @@ int ccdc_pipeline_fused(const ccdc_plan_t *plan, const void *V, void *X, void *P
         if (vec == 4) return run_pipeline<HybF32, 4>(plan, V, X, Phi, wide_final, st);
         if (vec == 2) return run_pipeline<HybF32, 2>(plan, V, X, Phi, wide_final, st);
         return run_pipeline<HybF32, 1>(plan, V, X, Phi, wide_final, st);
+    }
+    if (plan->mode == CCDC_BF16_SUM_XOR) {
+        if (vec == 4) return run_pipeline<HybBF16, 4>(plan, V, X, Phi, wide_final, st);
+        if (vec == 2) return run_pipeline<HybBF16, 2>(plan, V, X, Phi, wide_final, st);
+        return run_pipeline<HybBF16, 1>(plan, V, X, Phi, wide_final, st);
+    }
+    if (plan->mode == CCDC_F16_SUM_XOR) {
+        if (vec == 4) return run_pipeline<HybF16, 4>(plan, V, X, Phi, wide_final, st);
+        if (vec == 2) return run_pipeline<HybF16, 2>(plan, V, X, Phi, wide_final, st);
+        return run_pipeline<HybF16, 1>(plan, V, X, Phi, wide_final, st);
     }
     if (vec == 4) return run_pipeline<XorU32, 4>(plan, V, X, Phi, wide_final, st);
     if (vec == 2) return run_pipeline<XorU32, 2>(plan, V, X, Phi, wide_final, st);

@@ -230,6 +230,7 @@ namespace {
 // the receiver adds.
 int bind_compression(ccdc_plan_t *p, int64_t T, int mode)
 {
+    if (mode != CCDC_F32_SUM && mode != CCDC_U32_XOR) return CCDC_EINVAL;   // nothing is coded: no hybrid of it
     if (T > kMaxElems / p->c) return CCDC_ESIZE;
     const int64_t W = (int64_t)p->c * T;
     const int vec = (T % 4 == 0) ? 4 : 1;
@@ -280,7 +281,7 @@ int bind_compression(ccdc_plan_t *p, int64_t T, int mode)
 
 int bind_plan(ccdc_plan_t *p, int64_t T, int mode)
 {
-    if (!p || T < 1 || (mode != CCDC_F32_SUM && mode != CCDC_U32_XOR && mode != CCDC_F32_SUM_XOR)) return CCDC_EINVAL;
+    if (!p || T < 1 || mode < CCDC_F32_SUM || mode > CCDC_F16_SUM_XOR) return CCDC_EINVAL;
     if (p->compression) return bind_compression(p, T, mode);
     const int r = p->r, r1 = r + 1;
     if (T > kMaxElems / p->c) return CCDC_ESIZE;
