@@ -54,20 +54,24 @@ def measured_traffic(workload, mode, path):
     return int(1024 * (t["fetch_kib"] * t["fetch_scale"] + t["write_kib"] * t["write_scale"]))
 
 
-def algorithmic_bytes_shuffle(w, ell):
+def elem_bytes(mode):
+    return 2 if mode in ("bf16", "f16") else 4
+
+
+def algorithmic_bytes_shuffle(w, ell, eb=4):
     """Bytes one fused combine+encode+decode launch must move: every needed
     element of V once, every coded packet and every decoded packet once."""
     rounds, r1, W = w.G, w.r + 1, w.W
     reads = rounds * r1 * w.m * W
     writes = rounds * r1 * (ell + W)
-    return 4 * (reads + writes)
+    return eb * (reads + writes)
 
 
-def algorithmic_bytes_pipeline(w, ell):
+def algorithmic_bytes_pipeline(w, ell, eb=4):
     """Bytes the one-pass pipeline must move: all of V once (every intermediate
     value is either pre-combined for a round or added by its own reducer), every
     coded packet once, the outputs once."""
-    return 4 * (w.v_elems + w.G * (w.r + 1) * ell + w.Q * w.T)
+    return eb * (w.v_elems + w.G * (w.r + 1) * ell + w.Q * w.T)
 
 
 def cpu_baseline(w, mode, T_sample):
@@ -82,6 +86,9 @@ def cpu_baseline(w, mode, T_sample):
     rng = np.random.default_rng(1)
     if mode == "u32":
         V = generate_numpy(w.J, w.N, w.Q, T_sample, 1, "u32")
+    elif mode in ("bf16", "f16"):
+        from workloads import to_half_bits
+        V = to_half_bits((w.sigma * rng.standard_normal((w.J, w.N, w.Q, T_sample), dtype=np.float32)), mode)
     else:
         V = (w.sigma * rng.standard_normal((w.J, w.N, w.Q, T_sample), dtype=np.float32)).astype(np.float32)
     cp = O.CompressionPlan(w.K, w.r, w.Q, w.N) if w.compression else None
@@ -92,6 +99,8 @@ def cpu_baseline(w, mode, T_sample):
             cp.reduce(T_sample, V[0], cp.combine(T_sample, V[0]))
         elif mode == "h32":
             O.run_all_h32(op, T_sample, V)
+        elif mode in ("bf16", "f16"):
+            O.run_all_h16(op, T_sample, V, mode)
         else:
             O.run_all(op, T_sample, V)
         dt += time.perf_counter() - t0
@@ -109,7 +118,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cfg3_gradient")
-    ap.add_argument("--mode", default=None, help="f32 or u32 (default: the workload's first mode)")
+    ap.add_argument("--mode", default=None, help="f32, u32, h32, bf16 or f16 (default: the workload's first mode)")
     ap.add_argument("--path", default="pipeline", choices=["pipeline", "shuffle+reduce"],
                     help="pipeline: ccdc_pipeline_fused; shuffle+reduce: ccdc_shuffle_fused then ccdc_reduce")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -154,8 +163,9 @@ def main():
         args.path = "combine+reduce"      # the comparison scheme codes nothing
     plan = L.Plan(w.K, w.r, w.Q, w.N, jobs=w.jobs, compression=w.compression).bind(w.T, mode).upload()
     sh = plan.shapes()
-    dt = torch.int32 if mode == "u32" else torch.float32
-    V = generate_torch(w.J, w.N, w.Q, w.T, 1, "u32" if mode == "u32" else "f32", sigma=w.sigma, device="cuda")
+    eb = elem_bytes(mode)
+    dt = {"u32": torch.int32, "bf16": torch.bfloat16, "f16": torch.float16}.get(mode, torch.float32)
+    V = generate_torch(w.J, w.N, w.Q, w.T, 1, "f32" if mode == "h32" else mode, sigma=w.sigma, device="cuda")
     X = torch.empty(sh["X"], dtype=dt, device="cuda")
     D = torch.empty(sh["D"], dtype=dt, device="cuda") if args.path != "pipeline" else None
     Phi = torch.empty(sh["Phi"], dtype=dt, device="cuda")
@@ -194,11 +204,11 @@ def main():
     ms_per_step = 1e3 * elapsed / args.steps
     first_ms = sum(e[0].elapsed_time(e[1]) for e in evs) / args.steps
     second_ms = sum(e[1].elapsed_time(e[2]) for e in evs) / args.steps
-    v_bytes = w.v_bytes
+    v_bytes = eb * w.v_elems
     value = v_bytes / (ms_per_step * 1e-3) / 1e9
 
     if args.path == "pipeline":
-        alg = algorithmic_bytes_pipeline(w, plan.seg_len)
+        alg = algorithmic_bytes_pipeline(w, plan.seg_len, eb)
         kernel, kernel_ms = "k_pipeline (+ k_reduce_final when the rounds are chunked)", {"pipeline_fused": round(first_ms, 4)}
         path = "ccdc_pipeline_fused"
     elif args.path == "combine+reduce":
@@ -210,7 +220,7 @@ def main():
         kernel, kernel_ms = "k_combine", {"combine": round(first_ms, 4), "reduce": round(second_ms, 4)}
         path = "ccdc_combine + ccdc_reduce (compression-only comparison scheme)"
     else:
-        alg = algorithmic_bytes_shuffle(w, plan.seg_len)
+        alg = algorithmic_bytes_shuffle(w, plan.seg_len, eb)
         kernel, kernel_ms = "k_shuffle_fused", {"shuffle_fused": round(first_ms, 4), "reduce": round(second_ms, 4)}
         path = "ccdc_shuffle_fused + ccdc_reduce"
     achieved = alg / (first_ms * 1e-3) / 1e9
@@ -240,7 +250,7 @@ def main():
                      "traffic": measured_traffic(w.name, mode, args.path)},
     }
     if not args.no_cpu_baseline:
-        T_sample = args.cpu_sample_T or max(4, min(w.T, (1_000_000_000 // (4 * w.J * w.Q * w.N)) // 4 * 4))
+        T_sample = args.cpu_sample_T or max(4, min(w.T, (1_000_000_000 // (4 * w.J * w.Q * w.N)) // 8 * 8))
         out["cpu_baseline"] = cpu_baseline(w, mode, T_sample)
     plan.close()
     print(json.dumps(out), flush=True)

@@ -134,6 +134,21 @@ def test_state_and_argument_errors(lib):
     assert B.strerror(B.ESIZE) and B.strerror(-99) == "unknown status"
 
 
+def test_payload_modes(lib):
+    p = B.ccdc_plan(4, 2, 4, 12)
+    for name, code in B.MODES.items():
+        p.bind(24, name)
+        assert p.query(B.Q_MODE) == code and p.W == 24 and p.seg_len == 12
+        assert p._elem_bytes == (2 if name in ("bf16", "f16") else 4)
+    assert lib.ccdc_plan_bind(p._h, 24, 5) == B.EINVAL and lib.ccdc_plan_bind(p._h, 24, -1) == B.EINVAL
+    p.close()
+    cp = B.ccdc_plan_compression(4, 2, 4, 8)
+    for name, code in B.MODES.items():            # the uncoded scheme has no hybrid of sums and XOR-coded packets
+        want = B.OK if name in ("f32", "u32") else B.EINVAL
+        assert lib.ccdc_plan_bind(cp._h, 24, code) == want
+    cp.close()
+
+
 def test_binding_refuses_to_run_without_the_library(monkeypatch, tmp_path):
     monkeypatch.setattr(B, "_lib", None)
     monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "libccdc.so"))

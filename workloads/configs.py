@@ -57,11 +57,11 @@ class Workload:
 
 
 CONFIGS = {
-    "cfg1_tiny": Workload("cfg1_tiny", 4, 2, 4, 12, 256, 1.0, ("f32", "u32", "h32")),
+    "cfg1_tiny": Workload("cfg1_tiny", 4, 2, 4, 12, 256, 1.0, ("f32", "u32", "h32", "bf16", "f16")),
     "cfg2_k10": Workload("cfg2_k10", 10, 3, 10, 120, 4096, 1.0, ("f32", "u32", "h32")),
-    "cfg3_gradient": Workload("cfg3_gradient", 8, 2, 8, 28, 3_200_000, 0.01, ("f32", "h32")),
+    "cfg3_gradient": Workload("cfg3_gradient", 8, 2, 8, 28, 3_200_000, 0.01, ("f32", "h32", "bf16")),
     "cfg4_k16": Workload("cfg4_k16", 16, 3, 16, 560, 4096, 1.0, ("f32",)),
-    "cfg5_k24": Workload("cfg5_k24", 24, 4, 24, 10626, 2048, 1.0, ("f32", "u32", "h32")),
+    "cfg5_k24": Workload("cfg5_k24", 24, 4, 24, 10626, 2048, 1.0, ("f32", "u32", "h32", "bf16", "f16")),
     "jobs_k8": Workload("jobs_k8", 8, 2, 8, 9, 150_000, 1.0, ("f32", "u32"), jobs=True),
     # the gradient shape through the compression-only comparison scheme (4 batches of 7 files)
     "comp_gradient": Workload("comp_gradient", 8, 2, 8, 28, 3_200_000, 0.01, ("f32",), compression=True),
