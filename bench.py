@@ -31,9 +31,21 @@ METRIC = "GB/s of intermediate values through combine+encode+decode; % of HBM pe
 # whose hash is recorded with them; for any other source `traffic` is null.
 TRAFFIC = {
     ("cfg3_gradient", "f32", "pipeline"): {
-        "source_hash": "08c169f87ac24bc0", "fetch_kib": 1419547.2, "write_kib": 1150000.4, "fetch_scale": 2.0, "write_scale": 1.0},
+        "source_hash": "6828de0824b3da67", "fetch_kib": 1419692.9, "write_kib": 1150000.6, "fetch_scale": 2.0, "write_scale": 1.0},
     ("cfg5_k24", "f32", "pipeline"): {
-        "source_hash": "08c169f87ac24bc0", "fetch_kib": 1042226.7, "write_kib": 462096.0, "fetch_scale": 2.0, "write_scale": 1.0},
+        "source_hash": "6828de0824b3da67", "fetch_kib": 1042248.6, "write_kib": 462096.0, "fetch_scale": 2.0, "write_scale": 1.0},
+    ("cfg5_k24", "u32", "pipeline"): {
+        "source_hash": "6828de0824b3da67", "fetch_kib": 1042455.2, "write_kib": 462096.0, "fetch_scale": 2.0, "write_scale": 1.0},
+    ("cfg3_gradient", "bf16", "pipeline"): {
+        "source_hash": "6828de0824b3da67", "fetch_kib": 707262.4, "write_kib": 575000.4, "fetch_scale": 2.0, "write_scale": 1.0},
+    ("cfg5_k24", "bf16", "pipeline"): {
+        "source_hash": "6828de0824b3da67", "fetch_kib": 531576.1, "write_kib": 249480.0, "fetch_scale": 2.0, "write_scale": 1.0},
+    ("cfg3_gradient", "f32", "shuffle+reduce"): {
+        "source_hash": "6828de0824b3da67", "fetch_kib": 1050027.0, "write_kib": 3150288.4, "fetch_scale": 2.0, "write_scale": 1.0},
+    ("jobs_k8", "f32", "shuffle+reduce"): {
+        "source_hash": "6828de0824b3da67", "fetch_kib": 909516.2, "write_kib": 892661.6, "fetch_scale": 2.0, "write_scale": 1.0},
+    ("comp_gradient", "f32", "combine+reduce"): {
+        "source_hash": "6828de0824b3da67", "fetch_kib": 1050013.8, "write_kib": 300000.0, "fetch_scale": 2.0, "write_scale": 1.0},
 }
 
 
