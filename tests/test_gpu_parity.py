@@ -172,6 +172,29 @@ def test_edge_shapes(torch, L, K, r, Q, N, T, jobs, mode):
     run_case(torch, L, K, r, Q, N, T, mode, jobs=jobs, seed=K * 10 + r)
 
 
+def random_shape(rng):
+    """A valid (K, r, Q, N, T, jobs) drawn over the whole parameter space at small sizes."""
+    from math import comb
+    K = int(rng.integers(2, 10))
+    r = int(rng.integers(1, K))
+    jobs = bool(K <= 6 and rng.integers(0, 3) == 0)
+    c = int(rng.integers(1, 4))
+    nb = (r + 1) if jobs else comb(K, r)
+    m = int(rng.integers(1, 4))
+    while m * nb < K:
+        m += 1
+    T = int(rng.choice([1, 2, 3, 4, 5, 8, 12, 16, 24, 31, 64, 100, 128, 250, 256, 511, 520]))
+    return K, r, c * K, m * nb, T, jobs
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_shapes(torch, L, seed):
+    rng = np.random.default_rng(1000 + seed)
+    K, r, Q, N, T, jobs = random_shape(rng)
+    mode = ["u32", "f32", "h32"][seed % 3]
+    run_case(torch, L, K, r, Q, N, T, mode, jobs=jobs, seed=seed)
+
+
 def test_unaligned_pointers_take_the_scalar_path(torch, L):
     """Buffers that are only 4-byte aligned still work; others are refused."""
     K, r, Q, N, T, mode = 5, 2, 5, 10, 64, "u32"

@@ -129,6 +129,22 @@ def test_shapes(torch, L, K, r, Q, N, T, jobs, fmt):
     run_case(torch, L, K, r, Q, N, T, fmt, jobs=jobs, seed=K * 10 + r)
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_random_shapes(torch, L, seed):
+    from math import comb
+    rng = np.random.default_rng(2000 + seed)
+    K = int(rng.integers(2, 10))
+    r = int(rng.integers(1, K))
+    jobs = bool(K <= 6 and rng.integers(0, 3) == 0)
+    c = int(rng.integers(1, 4))
+    nb = (r + 1) if jobs else comb(K, r)
+    m = int(rng.integers(1, 4))
+    while m * nb < K:
+        m += 1
+    T = int(rng.choice([1, 2, 3, 4, 5, 8, 12, 16, 24, 31, 64, 100, 128, 250, 256, 511, 520]))
+    run_case(torch, L, K, r, c * K, m * nb, T, FORMATS[seed % 2], jobs=jobs, seed=seed)
+
+
 @pytest.mark.parametrize("fmt", FORMATS)
 def test_two_byte_aligned_pointers(torch, L, fmt):
     """Buffers that are only 2-byte aligned take the one-element path; odd addresses are refused."""
