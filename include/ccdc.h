@@ -163,7 +163,12 @@ const char *ccdc_strerror(int status);
 /*
  * The four stages.  All pointers are device pointers; see the buffer table
  * above for shapes.  Each needs an uploaded plan (CCDC_ESTATE otherwise) and
- * the plan's device to be current.
+ * the plan's device to be current.  The caller owns every buffer and keeps it
+ * alive until the stream has run the call; inputs are only read, outputs are
+ * written in full (no accumulation into what they held).  CCDC_EINVAL for a
+ * null pointer or one not aligned to the element size; pointers aligned to 16
+ * bytes (with T a multiple of 4, or of 8 for 2-byte elements) take the wide
+ * kernels, others the one-element kernels with the same results.
  */
 
 /* Pre-combining (Sec. IV-B): Vbar[u][b][e] = sum over the m files n of the
