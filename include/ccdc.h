@@ -209,6 +209,31 @@ int ccdc_shuffle_fused(const ccdc_plan_t *plan, const void *V, void *X, void *D,
  * use ccdc_shuffle_fused + ccdc_reduce there. */
 int ccdc_pipeline_fused(const ccdc_plan_t *plan, const void *V, void *X, void *Phi, void *stream);
 
+/*
+ * The node-local form of the path: what ONE node of the cluster does in the
+ * shuffle, from nothing but the files it stores and the coded packets it
+ * receives (Sec. IV-B, "for each k in K": pre-combine, split, code, multicast;
+ * then decode with locally computed side information and reduce).  V and X are
+ * the same arrays as above, but node k's calls read only the files k stores
+ * (its batches, Sec. IV-A) and the packets sent to k, so X plays the network.
+ * node = -1 runs every node in one launch: the emulation in which no result is
+ * shared between nodes (each of the r nodes storing a batch pre-combines it
+ * for itself).
+ *
+ * ccdc_node_encode writes the packets X[u][a] the node sends (rounds u it is
+ *   member a of); they equal ccdc_encode's bit for bit.
+ * ccdc_node_decode_reduce writes the node's c outputs of every job,
+ *   Phi[job][node*c*T ...]: its own files plus, for every round it is in, the
+ *   packet it decodes from the other members' coded packets; the decoded packet
+ *   is never stored.  Same row order as ccdc_reduce; uses the plan's workspace
+ *   when the sum is split (chunk sums are added in chunk order).
+ * Call ccdc_node_encode for all senders of a round before a receiver decodes it.
+ * Errors as the stage calls; CCDC_EINVAL for node outside -1..K-1, CCDC_ESTATE
+ * for plans of ccdc_plan_compression.
+ */
+int ccdc_node_encode(const ccdc_plan_t *plan, int node, const void *V, void *X, void *stream);
+int ccdc_node_decode_reduce(const ccdc_plan_t *plan, int node, const void *V, const void *X, void *Phi, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

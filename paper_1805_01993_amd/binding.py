@@ -29,7 +29,7 @@ ELEM_BYTES = {F32_SUM: 4, U32_XOR: 4, F32_SUM_XOR: 4, BF16_SUM_XOR: 2, F16_SUM_X
 EXPORTS = [
     "ccdc_plan", "ccdc_plan_jobs", "ccdc_plan_compression", "ccdc_plan_destroy", "ccdc_plan_bind", "ccdc_plan_upload",
     "ccdc_plan_query", "ccdc_strerror", "ccdc_combine", "ccdc_encode", "ccdc_decode", "ccdc_reduce",
-    "ccdc_shuffle_fused", "ccdc_pipeline_fused",
+    "ccdc_shuffle_fused", "ccdc_pipeline_fused", "ccdc_node_encode", "ccdc_node_decode_reduce",
 ]
 
 
@@ -78,6 +78,10 @@ def load_library():
         fn = getattr(lib, name)
         fn.restype = C.c_int
         fn.argtypes = [vp] + [vp] * nptr + [vp]
+    for name, nptr in (("ccdc_node_encode", 2), ("ccdc_node_decode_reduce", 3)):
+        fn = getattr(lib, name)
+        fn.restype = C.c_int
+        fn.argtypes = [vp, C.c_int] + [vp] * nptr + [vp]
     _lib = lib
     return lib
 
@@ -255,6 +259,16 @@ class Plan:
         _check(self._lib.ccdc_pipeline_fused(self._h, self._need(V, "V", "V"), self._need(X, "X", "X"),
                                              self._need(Phi, "Phi", "Phi"), _stream_ptr(stream)),
                "ccdc_pipeline_fused")
+
+    # ---- the node-local form: node = -1 runs every node
+    def node_encode(self, node, V, X, stream=None):
+        _check(self._lib.ccdc_node_encode(self._h, int(node), self._need(V, "V", "V"), self._need(X, "X", "X"),
+                                          _stream_ptr(stream)), "ccdc_node_encode")
+
+    def node_decode_reduce(self, node, V, X, Phi, stream=None):
+        _check(self._lib.ccdc_node_decode_reduce(self._h, int(node), self._need(V, "V", "V"), self._need(X, "X", "X"),
+                                                 self._need(Phi, "Phi", "Phi"), _stream_ptr(stream)),
+               "ccdc_node_decode_reduce")
 
 
 def ccdc_plan(K, r, Q, N):

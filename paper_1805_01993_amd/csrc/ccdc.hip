@@ -247,7 +247,7 @@ void release_device(ccdc_plan_t *p)
 {
     if (!p) return;
     if (p->uploaded || p->d_src_off || p->d_red_ptr || p->d_red_row || p->d_red_out || p->d_loc_row || p->d_member ||
-        p->d_workspace) {
+        p->d_row_files || p->d_node_rows || p->d_workspace) {
         int cur = -1;
         const bool sw = hipGetDevice(&cur) == hipSuccess && p->device >= 0 && cur != p->device &&
                         hipSetDevice(p->device) == hipSuccess;
@@ -258,12 +258,14 @@ void release_device(ccdc_plan_t *p)
         (void)hipFree(p->d_loc_row);
         (void)hipFree(p->d_member);
         (void)hipFree(p->d_row_files);
+        (void)hipFree(p->d_node_rows);
         (void)hipFree(p->d_workspace);
         if (sw) (void)hipSetDevice(cur);
     }
     p->d_src_off = p->d_red_ptr = p->d_red_row = p->d_red_out = p->d_loc_row = nullptr;
     p->d_member = nullptr;
     p->d_row_files = nullptr;
+    p->d_node_rows = nullptr;
     p->d_workspace = nullptr;
     p->uploaded = false;
     p->device = -1;
@@ -380,39 +382,6 @@ int run_reduce(const ccdc_plan_t *p, const void *V, const void *D, void *Phi, hi
     return launched();
 }
 
-// Dispatch on (mode, vec): F(algebra tag, vec tag).
-#define CCDC_DISPATCH(p, vec, CALL)                                   \
-    do {                                                              \
-        if ((p)->mode == CCDC_F32_SUM) {                              \
-            using A = SumF32;                                         \
-            if ((vec) == 4) { constexpr int VEC = 4; return CALL; }   \
-            constexpr int VEC = 1;                                    \
-            return CALL;                                              \
-        } else if ((p)->mode == CCDC_F32_SUM_XOR) {                   \
-            using A = HybF32;                                         \
-            if ((vec) == 4) { constexpr int VEC = 4; return CALL; }   \
-            constexpr int VEC = 1;                                    \
-            return CALL;                                              \
-        } else if ((p)->mode == CCDC_BF16_SUM_XOR) {                  \
-            using A = HybBF16;                                        \
-            if ((vec) == 8) { constexpr int VEC = 8; return CALL; }   \
-            if ((vec) == 4) { constexpr int VEC = 4; return CALL; }   \
-            constexpr int VEC = 1;                                    \
-            return CALL;                                              \
-        } else if ((p)->mode == CCDC_F16_SUM_XOR) {                   \
-            using A = HybF16;                                         \
-            if ((vec) == 8) { constexpr int VEC = 8; return CALL; }   \
-            if ((vec) == 4) { constexpr int VEC = 4; return CALL; }   \
-            constexpr int VEC = 1;                                    \
-            return CALL;                                              \
-        } else {                                                      \
-            using A = XorU32;                                         \
-            if ((vec) == 4) { constexpr int VEC = 4; return CALL; }   \
-            constexpr int VEC = 1;                                    \
-            return CALL;                                              \
-        }                                                             \
-    } while (0)
-
 }  // namespace
 
 // ------------------------------------------------------------ entry points
@@ -460,6 +429,7 @@ int ccdc_plan_upload(ccdc_plan_t *plan)
     if (rc == CCDC_OK) rc = to_device(plan->loc_row, &plan->d_loc_row);
     if (rc == CCDC_OK) rc = to_device(plan->round_member, &plan->d_member);
     if (rc == CCDC_OK && !plan->row_files.empty()) rc = to_device(plan->row_files, &plan->d_row_files);
+    if (rc == CCDC_OK && !plan->node_rows.empty()) rc = to_device(plan->node_rows, &plan->d_node_rows);
     if (rc == CCDC_OK && plan->workspace_bytes > 0 &&
         hipMalloc(&plan->d_workspace, plan->workspace_bytes) != hipSuccess) {
         plan->d_workspace = nullptr;

@@ -295,3 +295,37 @@ inline int launched()
 }
 
 }  // namespace ccdc
+
+// Dispatch on (payload mode, pack width): evaluates CALL with the algebra as type A and the
+// pack width as constant VEC, inside a function that has `using namespace ccdc`.
+#define CCDC_DISPATCH(p, vec, CALL)                                   \
+    do {                                                              \
+        if ((p)->mode == CCDC_F32_SUM) {                              \
+            using A = SumF32;                                         \
+            if ((vec) == 4) { constexpr int VEC = 4; return CALL; }   \
+            constexpr int VEC = 1;                                    \
+            return CALL;                                              \
+        } else if ((p)->mode == CCDC_F32_SUM_XOR) {                   \
+            using A = HybF32;                                         \
+            if ((vec) == 4) { constexpr int VEC = 4; return CALL; }   \
+            constexpr int VEC = 1;                                    \
+            return CALL;                                              \
+        } else if ((p)->mode == CCDC_BF16_SUM_XOR) {                  \
+            using A = HybBF16;                                        \
+            if ((vec) == 8) { constexpr int VEC = 8; return CALL; }   \
+            if ((vec) == 4) { constexpr int VEC = 4; return CALL; }   \
+            constexpr int VEC = 1;                                    \
+            return CALL;                                              \
+        } else if ((p)->mode == CCDC_F16_SUM_XOR) {                   \
+            using A = HybF16;                                         \
+            if ((vec) == 8) { constexpr int VEC = 8; return CALL; }   \
+            if ((vec) == 4) { constexpr int VEC = 4; return CALL; }   \
+            constexpr int VEC = 1;                                    \
+            return CALL;                                              \
+        } else {                                                      \
+            using A = XorU32;                                         \
+            if ((vec) == 4) { constexpr int VEC = 4; return CALL; }   \
+            constexpr int VEC = 1;                                    \
+            return CALL;                                              \
+        }                                                             \
+    } while (0)

@@ -162,6 +162,20 @@ int build_plan(int K, int r, int Q, int N, bool paper_jobs, ccdc_plan_t **out)
                 }
             }
         }
+        // packets each node sends: by symmetry nrows / K of them (C(K-1,r) rounds, times K-r for the J-job schedule)
+        p->rows_per_node = p->nrows / K;
+        p->node_rows.assign((size_t)p->nrows, 0);
+        std::vector<int64_t> fill((size_t)K, 0);
+        for (int64_t i = 0; i < p->nrows; i++) {
+            const int k = p->round_member[i];
+            if (fill[k] < p->rows_per_node) p->node_rows[(size_t)k * p->rows_per_node + fill[k]] = (int32_t)i;
+            fill[k]++;
+        }
+        for (int k = 0; k < K; k++)
+            if (fill[k] != p->rows_per_node) {
+                delete p;
+                return CCDC_EINVAL;
+            }
     } catch (const std::bad_alloc &) {
         delete p;
         return CCDC_ENOMEM;

@@ -32,6 +32,8 @@ struct ccdc_plan_s {
     std::vector<int32_t> batch_label;   // [nbatch][r]
     std::vector<int32_t> round_member;  // [nround][r+1]
     std::vector<int32_t> round_batch;   // [nround][r+1]
+    std::vector<int32_t> node_rows;     // [K][rows_per_node] packets (u*(r+1)+a) that node k sends, ascending
+    int64_t rows_per_node = 0;          // nrows / K: every node is in the same number of rounds
 
     // fixed by ccdc_plan_bind
     bool bound = false;
@@ -65,6 +67,7 @@ struct ccdc_plan_s {
     int64_t *d_loc_row = nullptr;
     int32_t *d_member = nullptr;
     int32_t *d_row_files = nullptr;     // null when every packet adds m files
+    int32_t *d_node_rows = nullptr;
     void *d_workspace = nullptr;
 };
 
