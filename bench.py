@@ -31,21 +31,23 @@ METRIC = "GB/s of intermediate values through combine+encode+decode; % of HBM pe
 # whose hash is recorded with them; for any other source `traffic` is null.
 TRAFFIC = {
     ("cfg3_gradient", "f32", "pipeline"): {
-        "source_hash": "6828de0824b3da67", "fetch_kib": 1419692.9, "write_kib": 1150000.6, "fetch_scale": 2.0, "write_scale": 1.0},
+        "source_hash": "564018742d673cd6", "fetch_kib": 1419543.0, "write_kib": 1150000.9, "fetch_scale": 2.0, "write_scale": 1.0},
     ("cfg5_k24", "f32", "pipeline"): {
-        "source_hash": "6828de0824b3da67", "fetch_kib": 1042248.6, "write_kib": 462096.0, "fetch_scale": 2.0, "write_scale": 1.0},
+        "source_hash": "564018742d673cd6", "fetch_kib": 1042264.3, "write_kib": 462096.0, "fetch_scale": 2.0, "write_scale": 1.0},
     ("cfg5_k24", "u32", "pipeline"): {
-        "source_hash": "6828de0824b3da67", "fetch_kib": 1042455.2, "write_kib": 462096.0, "fetch_scale": 2.0, "write_scale": 1.0},
+        "source_hash": "564018742d673cd6", "fetch_kib": 1042461.8, "write_kib": 462096.0, "fetch_scale": 2.0, "write_scale": 1.0},
     ("cfg3_gradient", "bf16", "pipeline"): {
-        "source_hash": "6828de0824b3da67", "fetch_kib": 707262.4, "write_kib": 575000.4, "fetch_scale": 2.0, "write_scale": 1.0},
+        "source_hash": "564018742d673cd6", "fetch_kib": 707213.6, "write_kib": 575000.3, "fetch_scale": 2.0, "write_scale": 1.0},
     ("cfg5_k24", "bf16", "pipeline"): {
-        "source_hash": "6828de0824b3da67", "fetch_kib": 531576.1, "write_kib": 249480.0, "fetch_scale": 2.0, "write_scale": 1.0},
+        "source_hash": "564018742d673cd6", "fetch_kib": 531579.2, "write_kib": 249480.0, "fetch_scale": 2.0, "write_scale": 1.0},
     ("cfg3_gradient", "f32", "shuffle+reduce"): {
-        "source_hash": "6828de0824b3da67", "fetch_kib": 1050027.0, "write_kib": 3150288.4, "fetch_scale": 2.0, "write_scale": 1.0},
+        "source_hash": "564018742d673cd6", "fetch_kib": 1050027.0, "write_kib": 3150269.0, "fetch_scale": 2.0, "write_scale": 1.0},
     ("jobs_k8", "f32", "shuffle+reduce"): {
-        "source_hash": "6828de0824b3da67", "fetch_kib": 909516.2, "write_kib": 892661.6, "fetch_scale": 2.0, "write_scale": 1.0},
+        "source_hash": "564018742d673cd6", "fetch_kib": 909432.2, "write_kib": 892655.3, "fetch_scale": 2.0, "write_scale": 1.0},
     ("comp_gradient", "f32", "combine+reduce"): {
-        "source_hash": "6828de0824b3da67", "fetch_kib": 1050013.8, "write_kib": 300000.0, "fetch_scale": 2.0, "write_scale": 1.0},
+        "source_hash": "564018742d673cd6", "fetch_kib": 1050013.7, "write_kib": 300000.0, "fetch_scale": 2.0, "write_scale": 1.0},
+    ("cfg3_gradient", "f32", "node"): {
+        "source_hash": "564018742d673cd6", "fetch_kib": 2450059.8, "write_kib": 100000.0, "fetch_scale": 2.0, "write_scale": 1.0},
 }
 
 
@@ -131,8 +133,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cfg3_gradient")
     ap.add_argument("--mode", default=None, help="f32, u32, h32, bf16 or f16 (default: the workload's first mode)")
-    ap.add_argument("--path", default="pipeline", choices=["pipeline", "shuffle+reduce"],
-                    help="pipeline: ccdc_pipeline_fused; shuffle+reduce: ccdc_shuffle_fused then ccdc_reduce")
+    ap.add_argument("--path", default="pipeline", choices=["pipeline", "shuffle+reduce", "node"],
+                    help="pipeline: ccdc_pipeline_fused; shuffle+reduce: ccdc_shuffle_fused then ccdc_reduce; "
+                         "node: ccdc_node_encode then ccdc_node_decode_reduce for every node (nothing shared "
+                         "between the emulated nodes)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-T", type=int, default=0)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -179,7 +183,7 @@ def main():
     dt = {"u32": torch.int32, "bf16": torch.bfloat16, "f16": torch.float16}.get(mode, torch.float32)
     V = generate_torch(w.J, w.N, w.Q, w.T, 1, "f32" if mode == "h32" else mode, sigma=w.sigma, device="cuda")
     X = torch.empty(sh["X"], dtype=dt, device="cuda")
-    D = torch.empty(sh["D"], dtype=dt, device="cuda") if args.path != "pipeline" else None
+    D = torch.empty(sh["D"], dtype=dt, device="cuda") if args.path not in ("pipeline", "node") else None
     Phi = torch.empty(sh["Phi"], dtype=dt, device="cuda")
     stream = torch.cuda.current_stream()
 
@@ -190,6 +194,11 @@ def main():
             plan.pipeline_fused(V, X, Phi, stream=stream)
             if events is not None:
                 events[1].record(stream)
+        elif args.path == "node":
+            plan.node_encode(-1, V, X, stream=stream)
+            if events is not None:
+                events[1].record(stream)
+            plan.node_decode_reduce(-1, V, X, Phi, stream=stream)
         elif args.path == "combine+reduce":
             plan.combine(V, D, stream=stream)          # D: the uncoded packets, sent as they are
             if events is not None:
@@ -231,6 +240,15 @@ def main():
         alg = 4 * w.W * (rows_files + plan.query(L.binding.Q_NROWS))
         kernel, kernel_ms = "k_combine", {"combine": round(first_ms, 4), "reduce": round(second_ms, 4)}
         path = "ccdc_combine + ccdc_reduce (compression-only comparison scheme)"
+    elif args.path == "node":
+        # what every node reads for itself: per (round, receiver) the r coded segments meant for it (one packet
+        # length) and the r-1 other packets it cancels, pre-combined from m files each; its own files; its outputs
+        rows = w.G * (w.r + 1)
+        alg = eb * (rows * (w.W + (w.r - 1) * w.m * w.W) + w.r * w.v_elems // w.K + w.J * w.Q * w.T)
+        kernel, kernel_ms = "k_node_decode_reduce", {"node_encode": round(first_ms, 4),
+                                                     "node_decode_reduce": round(second_ms, 4)}
+        path = "ccdc_node_encode + ccdc_node_decode_reduce, every node (per-node-faithful accounting)"
+        first_ms, second_ms = second_ms, first_ms      # the dominant kernel is the second call
     else:
         alg = algorithmic_bytes_shuffle(w, plan.seg_len, eb)
         kernel, kernel_ms = "k_shuffle_fused", {"shuffle_fused": round(first_ms, 4), "reduce": round(second_ms, 4)}
