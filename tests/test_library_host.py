@@ -37,6 +37,28 @@ def test_every_declared_symbol_is_exported(lib):
     assert sorted(B.EXPORTS) == names        # the binding covers the whole header
 
 
+def test_header_is_plain_c_and_the_binding_uses_its_numbers(tmp_path):
+    """include/ccdc.h compiles as C11 on its own, and every enumerator the binding
+    hard-codes has the value the header gives it."""
+    import subprocess
+    text = open(os.path.join(ROOT, "include", "ccdc.h")).read()
+    names = sorted(set(re.findall(r"\b(CCDC_[A-Z0-9_]+)\b", re.sub(r"/\*.*?\*/", "", text, flags=re.S))) - {"CCDC_H"})
+    prog = '#include "ccdc.h"\n#include <stdio.h>\nint main(void) {\n' + "".join(
+        f'    printf("{n} %d\\n", (int){n});\n' for n in names) + "    return 0;\n}\n"
+    src, exe = tmp_path / "enums.c", tmp_path / "enums"
+    src.write_text(prog)
+    subprocess.run(["gcc", "-std=c11", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)],
+                   check=True)
+    got = dict(line.split() for line in subprocess.run([str(exe)], capture_output=True, text=True, check=True)
+               .stdout.splitlines())
+    got = {k: int(v) for k, v in got.items()}
+    for name, value in got.items():
+        short = name[len("CCDC_"):]
+        assert hasattr(B, short), f"the binding has no constant for {name}"
+        assert getattr(B, short) == value, name
+    assert len(got) >= 45
+
+
 def test_library_does_not_link_the_oracle():
     import subprocess
     needed = subprocess.run(["readelf", "-d", B.LIB_PATH], capture_output=True, text=True).stdout
