@@ -99,7 +99,9 @@ enum ccdc_query {
     CCDC_Q_NODE_BATCH,       /* int32_t[K]         batch stored by node k       (compression)   */
     CCDC_Q_PACKET_RECV,      /* int32_t[NROWS]     receiver of packet i         (compression)   */
     CCDC_Q_PACKET_BATCH,     /* int32_t[NROWS]     batch packet i pre-combines  (compression)   */
-    CCDC_Q_PACKET_SEND       /* int32_t[NROWS]     node that sends packet i     (compression)   */
+    CCDC_Q_PACKET_SEND,      /* int32_t[NROWS]     node that sends packet i     (compression)   */
+    CCDC_Q_ROWS_PER_NODE,    /* packets every node sends: NROWS / K                   (coded plans)   */
+    CCDC_Q_NODE_ROWS         /* int32_t[K][ROWS_PER_NODE] packets u*(r+1)+a node k sends, ascending   */
 };
 
 /*

@@ -24,7 +24,8 @@ ELEM_BYTES = {F32_SUM: 4, U32_XOR: 4, F32_SUM_XOR: 4, BF16_SUM_XOR: 2, F16_SUM_X
  Q_SCHEDULED_ELEMS, Q_CLOSED_FORM_NUM, Q_CLOSED_FORM_DEN, Q_V_ELEMS, Q_VBAR_ELEMS, Q_X_ELEMS,
  Q_D_ELEMS, Q_PHI_ELEMS, Q_WORKSPACE_BYTES) = range(22)
 (Q_PACKET_LEN, Q_BATCH_JOB, Q_BATCH_FILE0, Q_BATCH_LABEL, Q_ROUND_MEMBER, Q_ROUND_BATCH) = range(64, 70)
-(Q_NROWS, Q_SCHEME, Q_BATCH_FIRST, Q_NODE_BATCH, Q_PACKET_RECV, Q_PACKET_BATCH, Q_PACKET_SEND) = range(128, 135)
+(Q_NROWS, Q_SCHEME, Q_BATCH_FIRST, Q_NODE_BATCH, Q_PACKET_RECV, Q_PACKET_BATCH, Q_PACKET_SEND,
+ Q_ROWS_PER_NODE, Q_NODE_ROWS) = range(128, 137)
 
 EXPORTS = [
     "ccdc_plan", "ccdc_plan_jobs", "ccdc_plan_compression", "ccdc_plan_destroy", "ccdc_plan_bind", "ccdc_plan_upload",
@@ -200,6 +201,10 @@ class Plan:
             "round_member": self.query_table(Q_ROUND_MEMBER, (R, r + 1), np.int32),
             "round_batch": self.query_table(Q_ROUND_BATCH, (R, r + 1), np.int32),
         }
+
+    def node_rows(self):
+        """[K][rows per node]: the packets u*(r+1)+a each node sends (coded plans)."""
+        return self.query_table(Q_NODE_ROWS, (self.K, self.query(Q_ROWS_PER_NODE)), np.int32)
 
     def packet_len(self):
         return self.query_table(Q_PACKET_LEN, (1 if self.compression else self.r + 1,), np.int64)

@@ -267,6 +267,8 @@ void release_device(ccdc_plan_t *p)
     p->d_row_files = nullptr;
     p->d_node_rows = nullptr;
     p->d_workspace = nullptr;
+    p->pipe_kernel = nullptr;
+    p->pipe_chunks = 0;
     p->uploaded = false;
     p->device = -1;
 }
@@ -475,6 +477,8 @@ int ccdc_plan_query(const ccdc_plan_t *p, int what, void *out, size_t out_bytes)
     case CCDC_Q_PACKET_RECV: return table(p->pkt_recv.data(), p->pkt_recv.size() * 4);
     case CCDC_Q_PACKET_BATCH: return table(p->pkt_batch.data(), p->pkt_batch.size() * 4);
     case CCDC_Q_PACKET_SEND: return table(p->pkt_send.data(), p->pkt_send.size() * 4);
+    case CCDC_Q_ROWS_PER_NODE: return scalar(p->rows_per_node);
+    case CCDC_Q_NODE_ROWS: return table(p->node_rows.data(), p->node_rows.size() * 4);
     case CCDC_Q_BATCH_JOB: return table(p->batch_job.data(), p->batch_job.size() * 4);
     case CCDC_Q_BATCH_FILE0: return table(p->batch_file0.data(), p->batch_file0.size() * 4);
     case CCDC_Q_BATCH_LABEL: return table(p->batch_label.data(), p->batch_label.size() * 4);

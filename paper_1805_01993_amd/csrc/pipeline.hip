@@ -253,6 +253,8 @@ __global__ __launch_bounds__(ccdc::kPipeLanes) void k_pipeline(
 template <class KernelT>
 int chunks_for(const ccdc_plan_t *p, KernelT kernel, uint32_t tiles, size_t lds)
 {
+    const void *key = reinterpret_cast<const void *>(kernel);
+    if (p->pipe_kernel == key && p->pipe_chunks > 0) return p->pipe_chunks;
     int per_cu = 0, cus = 0, dev = 0;
     if (hipGetDevice(&dev) != hipSuccess ||
         hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
@@ -265,6 +267,8 @@ int chunks_for(const ccdc_plan_t *p, KernelT kernel, uint32_t tiles, size_t lds)
     int64_t chunks = slots / tiles;
     if (chunks < 1) chunks = 1;
     if (chunks > p->pipe_max_chunks) chunks = p->pipe_max_chunks;
+    p->pipe_kernel = key;
+    p->pipe_chunks = (int)chunks;
     return (int)chunks;
 }
 

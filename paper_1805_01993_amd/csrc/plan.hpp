@@ -69,6 +69,11 @@ struct ccdc_plan_s {
     int32_t *d_row_files = nullptr;     // null when every packet adds m files
     int32_t *d_node_rows = nullptr;
     void *d_workspace = nullptr;
+
+    // launch geometry of the one-pass kernel last used on this device (an occupancy
+    // query answers it; remembered so that repeated calls do not ask again)
+    mutable const void *pipe_kernel = nullptr;
+    mutable int pipe_chunks = 0;
 };
 
 namespace ccdc {

@@ -99,6 +99,28 @@ def test_plan_tables_equal_the_oracles(lib, jobs):
     assert n == len(SWEEP)
 
 
+@pytest.mark.parametrize("jobs", [False, True])
+def test_node_rows_list_what_each_node_sends(lib, jobs):
+    """Every member of every round sends one packet (coded-packet equation of Sec. IV-B):
+    node k's list is exactly the packets (round u, position a) with s_a = k, ascending."""
+    from math import comb
+    for (K, r, c, m) in SWEEP[::3]:
+        nb = (r + 1) if jobs else comb(K, r)
+        while m * nb < K:
+            m += 1
+        p = B.Plan(K, r, c * K, m * nb, jobs=jobs)
+        o = O.build_plan(K, r, c * K, m * nb, "paper" if jobs else "single")
+        rows = p.node_rows()
+        member = o.round_member.reshape(-1)
+        assert rows.shape == (K, member.size // K)
+        for k in range(K):
+            assert rows[k].tolist() == np.flatnonzero(member == k).tolist()
+        p.close()
+    cp = B.ccdc_plan_compression(4, 2, 4, 8)
+    assert cp.query(B.Q_ROWS_PER_NODE) == 0
+    cp.close()
+
+
 def test_workload_plans(lib):
     from workloads import CONFIGS
     for w in CONFIGS.values():
