@@ -390,7 +390,7 @@ int bind_plan(ccdc_plan_t *p, int64_t T, int mode)
         std::vector<int64_t> loc;
         if (pipe_ok) {
             if (T % 4 == 0 && (int64_t)p->K * r * 16 * kPipeLanes <= kPipeGoodLds) pipe_vec = 4;
-            else if (T % 2 == 0 && (int64_t)p->K * r * 8 * kPipeLanes <= kPipeGoodLds) pipe_vec = 2;
+            else if (T % 2 == 0 && (int64_t)p->K * r * 8 * kPipeLanes <= kPipeGoodLdsHalf) pipe_vec = 2;
             // chunk partials are written and read once more: keep them under ~1/4 of |V|
             const double v = (double)p->N * p->Q * (double)T, kw = (double)p->K * (double)W;
             pipe_cap = std::max<int64_t>(1, std::min<int64_t>({(int64_t)1024, p->nround, (int64_t)(0.125 * v / kw)}));
