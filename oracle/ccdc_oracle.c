@@ -245,6 +245,49 @@ orc_plan *orc_plan_select_rounds(const orc_plan *src, const int64_t *rounds, int
     return p;
 }
 
+/* Sec. IV: with J = gamma * C(K, r+1) jobs the scheme works on C(K, r+1) jobs at
+ * a time and repeats the same operations gamma times.  Repetition g takes jobs
+ * g*J1 .. g*J1+J1-1 (J1 = jobs of the plan given) with the same placement and
+ * the same rounds. */
+orc_plan *orc_plan_repeat(const orc_plan *src, int gamma)
+{
+    if (!src || gamma < 1) return NULL;
+    const int r = src->r, r1 = src->r + 1;
+    if ((int64_t)src->J * gamma > INT32_MAX || src->n_batch * gamma > INT32_MAX || src->n_round * gamma > INT32_MAX)
+        return NULL;
+    orc_plan *p = (orc_plan *)calloc(1, sizeof(orc_plan));
+    if (!p) return NULL;
+    *p = *src;
+    p->J = src->J * gamma;
+    p->n_batch = src->n_batch * gamma;
+    p->n_round = src->n_round * gamma;
+    const size_t nb = (size_t)p->n_batch, nr = (size_t)p->n_round;
+    p->batch_job = (int *)malloc(sizeof(int) * nb);
+    p->batch_file0 = (int *)malloc(sizeof(int) * nb);
+    p->batch_label = (int *)malloc(sizeof(int) * nb * (size_t)r);
+    p->round_member = (int *)malloc(sizeof(int) * nr * (size_t)r1);
+    p->round_batch = (int *)malloc(sizeof(int) * nr * (size_t)r1);
+    if (!p->batch_job || !p->batch_file0 || !p->batch_label || !p->round_member || !p->round_batch) {
+        orc_plan_free(p);
+        return NULL;
+    }
+    for (int g = 0; g < gamma; g++) {
+        for (int64_t b = 0; b < src->n_batch; b++) {
+            const int64_t bt = g * src->n_batch + b;
+            p->batch_job[bt] = g * src->J + src->batch_job[b];
+            p->batch_file0[bt] = src->batch_file0[b];
+            for (int s = 0; s < r; s++) p->batch_label[bt * r + s] = src->batch_label[b * r + s];
+        }
+        for (int64_t u = 0; u < src->n_round; u++)
+            for (int b = 0; b < r1; b++) {
+                const int64_t i = (g * src->n_round + u) * r1 + b;
+                p->round_member[i] = src->round_member[u * r1 + b];
+                p->round_batch[i] = (int)(g * src->n_batch + src->round_batch[u * r1 + b]);
+            }
+    }
+    return p;
+}
+
 /* Sec. IV-B says the packet is split evenly into r segments and silently
  * assumes r | W.  Reading used here: if 4r | W the split is exact; otherwise
  * ell = ceil(W/r) rounded up to a multiple of 4 elements, segment rho covers

@@ -83,6 +83,9 @@ orc_plan *orc_plan_build(int K, int r, int Q, int N, int schedule, const int *ba
 void orc_plan_free(orc_plan *p);
 /* Same batches, only the listed rounds (for sampling a large schedule); NULL on bad index. */
 orc_plan *orc_plan_select_rounds(const orc_plan *src, const int64_t *rounds, int64_t n);
+/* J = gamma * (jobs of src): the same placement and rounds repeated gamma times on
+ * consecutive blocks of jobs (Sec. IV, "repeats the same operations gamma times"). */
+orc_plan *orc_plan_repeat(const orc_plan *src, int gamma);
 
 /* Segment length ell for a packet of W elements cut into r segments. */
 int64_t orc_segment_len(int64_t W, int r);

@@ -61,6 +61,8 @@ def _load():
     lib.orc_plan_build.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_int), C.c_int]
     lib.orc_plan_select_rounds.restype = P
     lib.orc_plan_select_rounds.argtypes = [P, C.POINTER(C.c_int64), C.c_int64]
+    lib.orc_plan_repeat.restype = P
+    lib.orc_plan_repeat.argtypes = [P, C.c_int]
     lib.orc_plan_free.restype = None
     lib.orc_plan_free.argtypes = [P]
     lib.orc_segment_len.restype = C.c_int64
@@ -127,10 +129,11 @@ class OraclePlan:
                 "D": (R, r1, W), "Phi": (self.J, self.Q, T)}
 
 
-def build_plan(K, r, Q, N, schedule="single", batch_order=None):
+def build_plan(K, r, Q, N, schedule="single", batch_order=None, gamma=1):
     """schedule: "single" (one job, one batch per r-subset) or "paper" (J=C(K,r+1) jobs).
 
-    batch_order: one permutation (shared) or a list of J permutations (one per job)."""
+    batch_order: one permutation (shared) or a list of J permutations (one per job).
+    gamma: the whole scheme repeated on gamma consecutive blocks of jobs (Sec. IV)."""
     lib = _load()
     sched = {"single": 0, "paper": 1}[schedule]
     order, sets = None, 0
@@ -141,6 +144,12 @@ def build_plan(K, r, Q, N, schedule="single", batch_order=None):
     ptr = lib.orc_plan_build(K, r, Q, N, sched, order, sets)
     if not ptr:
         raise ValueError(f"invalid parameters K={K} r={r} Q={Q} N={N} schedule={schedule}")
+    if gamma != 1:
+        once = ptr
+        ptr = lib.orc_plan_repeat(once, int(gamma))
+        lib.orc_plan_free(once)
+        if not ptr:
+            raise ValueError(f"invalid repetition count gamma={gamma}")
     return OraclePlan(ptr)
 
 

@@ -209,3 +209,30 @@ def test_full_size_shapes():
             continue
         p = O.build_plan(w.K, w.r, w.Q, w.N)
         assert p.n_round == comb(w.K, w.r + 1) and p.n_batch == comb(w.K, w.r) and p.m == w.m
+
+
+@pytest.mark.parametrize("K,r,gamma", [(4, 2, 2), (5, 2, 3), (4, 3, 4), (6, 1, 2)])
+def test_repeated_scheme(K, r, gamma):
+    """J = gamma*C(K, r+1) jobs (Sec. IV): the scheme works on C(K, r+1) jobs at a time and
+    repeats the same operations gamma times; the load per job is Theorem 1's."""
+    from fractions import Fraction
+    N = (r + 1) * max(1, -(-K // (r + 1)))
+    one = O.build_plan(K, r, 2 * K, N, "paper")
+    rep = O.build_plan(K, r, 2 * K, N, "paper", gamma=gamma)
+    G = comb(K, r + 1)
+    assert one.J == G and rep.J == gamma * G and rep.n_round == gamma * one.n_round and rep.n_batch == gamma * one.n_batch
+    for g in range(gamma):
+        b = slice(g * one.n_batch, (g + 1) * one.n_batch)
+        u = slice(g * one.n_round, (g + 1) * one.n_round)
+        assert np.array_equal(rep.batch_job[b], one.batch_job + g * G)          # the next block of jobs ...
+        assert np.array_equal(rep.batch_file0[b], one.batch_file0)              # ... placed the same way
+        assert np.array_equal(rep.batch_label[b], one.batch_label)
+        assert np.array_equal(rep.round_member[u], one.round_member)            # ... in the same rounds
+        assert np.array_equal(rep.round_batch[u], one.round_batch + g * one.n_batch)
+    # every job's files are each stored r times, |M_k| = mu*J*N
+    assert [len(stored_files(rep, k)) for k in range(K)] == [r * rep.J * N // K] * K
+    T = 4 * r
+    mu = Fraction(r, K)
+    assert Fraction(O.scheduled_elems(rep, T), rep.J * rep.Q * T) == (1 - mu) * (mu * K + 1) / (mu * K)
+    with pytest.raises(ValueError):
+        O.build_plan(K, r, 2 * K, N, "paper", gamma=0)

@@ -298,3 +298,13 @@ def test_h32_agrees_with_the_real_algebra_on_exact_inputs():
     assert np.array_equal(h["Phi"], f["Phi"])
     # but the coded packets differ in kind: XOR of patterns is not the pattern of the sum
     assert not np.array_equal(h["X"], bits(f["X"].astype(np.float32)))
+
+
+@pytest.mark.parametrize("mode", ["u32", "f32"])
+def test_repeated_scheme_recovers_every_output(mode):
+    """gamma repetitions on consecutive blocks of jobs (Sec. IV): every job's outputs are eq. (1)."""
+    p = O.build_plan(4, 2, 8, 6, "paper", gamma=3)
+    assert p.J == 12
+    V = make_inputs(p, 5, mode, seed=77)
+    art = O.run_all(p, 5, V)
+    assert np.array_equal(art["Phi"], O.direct(p, 5, V)) and np.array_equal(art["D"], art["Vbar"])
