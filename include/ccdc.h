@@ -121,6 +121,10 @@ enum ccdc_query {
  */
 int ccdc_plan(int K, int r, int Q, int N, ccdc_plan_t **out);
 int ccdc_plan_jobs(int K, int r, int Q, int N, ccdc_plan_t **out);
+/* J = gamma*C(K,r+1) jobs (Sec. IV): the scheme of ccdc_plan_jobs repeated on gamma consecutive
+ * blocks of C(K,r+1) jobs, same placement and rounds in each; R and the tables grow gamma-fold.
+ * CCDC_EINVAL for gamma < 1. */
+int ccdc_plan_jobs_repeated(int K, int r, int Q, int N, int gamma, ccdc_plan_t **out);
 
 /*
  * The comparison scheme that only pre-combines (appendix of the paper), one job,

@@ -28,7 +28,7 @@ ELEM_BYTES = {F32_SUM: 4, U32_XOR: 4, F32_SUM_XOR: 4, BF16_SUM_XOR: 2, F16_SUM_X
  Q_ROWS_PER_NODE, Q_NODE_ROWS) = range(128, 137)
 
 EXPORTS = [
-    "ccdc_plan", "ccdc_plan_jobs", "ccdc_plan_compression", "ccdc_plan_destroy", "ccdc_plan_bind", "ccdc_plan_upload",
+    "ccdc_plan", "ccdc_plan_jobs", "ccdc_plan_jobs_repeated", "ccdc_plan_compression", "ccdc_plan_destroy", "ccdc_plan_bind", "ccdc_plan_upload",
     "ccdc_plan_query", "ccdc_strerror", "ccdc_combine", "ccdc_encode", "ccdc_decode", "ccdc_reduce",
     "ccdc_shuffle_fused", "ccdc_pipeline_fused", "ccdc_node_encode", "ccdc_node_decode_reduce",
 ]
@@ -62,6 +62,8 @@ def load_library():
     lib.ccdc_plan.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, C.POINTER(vp)]
     lib.ccdc_plan_jobs.restype = C.c_int
     lib.ccdc_plan_jobs.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, C.POINTER(vp)]
+    lib.ccdc_plan_jobs_repeated.restype = C.c_int
+    lib.ccdc_plan_jobs_repeated.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.POINTER(vp)]
     lib.ccdc_plan_compression.restype = C.c_int
     lib.ccdc_plan_compression.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, C.POINTER(vp)]
     lib.ccdc_plan_destroy.restype = None
@@ -115,11 +117,16 @@ def _stream_ptr(stream):
 class Plan:
     """Owns one ccdc_plan_t.  Methods mirror the C entry points."""
 
-    def __init__(self, K, r, Q, N, jobs=False, compression=False):
+    def __init__(self, K, r, Q, N, jobs=False, compression=False, gamma=1):
         lib = load_library()
         h = C.c_void_p()
-        name = "ccdc_plan_compression" if compression else ("ccdc_plan_jobs" if jobs else "ccdc_plan")
-        _check(getattr(lib, name)(K, r, Q, N, C.byref(h)), name)
+        if gamma != 1:
+            if not jobs:
+                raise ValueError("gamma repeats the J-job schedule: pass jobs=True")
+            _check(lib.ccdc_plan_jobs_repeated(K, r, Q, N, int(gamma), C.byref(h)), "ccdc_plan_jobs_repeated")
+        else:
+            name = "ccdc_plan_compression" if compression else ("ccdc_plan_jobs" if jobs else "ccdc_plan")
+            _check(getattr(lib, name)(K, r, Q, N, C.byref(h)), name)
         self._h = h
         self.compression = bool(compression)
         self._lib = lib
@@ -284,6 +291,11 @@ def ccdc_plan(K, r, Q, N):
 def ccdc_plan_jobs(K, r, Q, N):
     """The paper's J = C(K, r+1)-job placement and two-stage schedule."""
     return Plan(K, r, Q, N, jobs=True)
+
+
+def ccdc_plan_jobs_repeated(K, r, Q, N, gamma):
+    """The J-job scheme repeated on gamma consecutive blocks of C(K, r+1) jobs."""
+    return Plan(K, r, Q, N, jobs=True, gamma=gamma)
 
 
 def ccdc_plan_compression(K, r, Q, N):

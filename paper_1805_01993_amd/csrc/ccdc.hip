@@ -389,9 +389,14 @@ int run_reduce(const ccdc_plan_t *p, const void *V, const void *D, void *Phi, hi
 // ------------------------------------------------------------ entry points
 extern "C" {
 
-int ccdc_plan(int K, int r, int Q, int N, ccdc_plan_t **out) { return ccdc::build_plan(K, r, Q, N, false, out); }
+int ccdc_plan(int K, int r, int Q, int N, ccdc_plan_t **out) { return ccdc::build_plan(K, r, Q, N, false, 1, out); }
 
-int ccdc_plan_jobs(int K, int r, int Q, int N, ccdc_plan_t **out) { return ccdc::build_plan(K, r, Q, N, true, out); }
+int ccdc_plan_jobs(int K, int r, int Q, int N, ccdc_plan_t **out) { return ccdc::build_plan(K, r, Q, N, true, 1, out); }
+
+int ccdc_plan_jobs_repeated(int K, int r, int Q, int N, int gamma, ccdc_plan_t **out)
+{
+    return ccdc::build_plan(K, r, Q, N, true, gamma, out);
+}
 
 int ccdc_plan_compression(int K, int r, int Q, int N, ccdc_plan_t **out)
 {

@@ -62,10 +62,11 @@ void lex_unrank(const Binom &C, int n, int k, int64_t rank, int *s)
 
 }  // namespace
 
-int build_plan(int K, int r, int Q, int N, bool paper_jobs, ccdc_plan_t **out)
+int build_plan(int K, int r, int Q, int N, bool paper_jobs, int gamma, ccdc_plan_t **out)
 {
     if (!out) return CCDC_EINVAL;
     *out = nullptr;
+    if (gamma < 1 || (gamma > 1 && !paper_jobs)) return CCDC_EINVAL;
     // Sec. III network model (K | Q, K <= N) and Theorem 1 (mu*K in 1..K-1)
     if (K < 2 || r < 1 || r > K - 1 || Q < 1 || N < 1 || Q % K != 0 || K > N) return CCDC_EINVAL;
     if (K > 4096) return CCDC_ESIZE;
@@ -78,7 +79,7 @@ int build_plan(int K, int r, int Q, int N, bool paper_jobs, ccdc_plan_t **out)
     if (N % per_job != 0) return CCDC_EINVAL;                 // Sec. IV-A: even batches
     const int64_t nround = paper_jobs ? G * (K - r) : G;
     const int64_t nbatch = paper_jobs ? G * r1 : nlabel;
-    if (nround * r1 > kMaxTable || nbatch * r > kMaxTable) return CCDC_ESIZE;
+    if (nround * r1 > kMaxTable / gamma || nbatch * r > kMaxTable / gamma || G > kMaxTable / gamma) return CCDC_ESIZE;
 
     ccdc_plan_t *p = new (std::nothrow) ccdc_plan_t;
     if (!p) return CCDC_ENOMEM;
@@ -159,6 +160,32 @@ int build_plan(int K, int r, int Q, int N, bool paper_jobs, ccdc_plan_t **out)
                         p->round_batch[u * r1 + b] = (int32_t)(jb * r1 + (r - pos));
                     }
                     u++;
+                }
+            }
+        }
+        // J = gamma * C(K, r+1) jobs (Sec. IV): the same placement and the same rounds
+        // again for every further block of C(K, r+1) jobs
+        if (gamma > 1) {
+            const int64_t nb1 = p->nbatch, nr1 = p->nround;
+            const int J1 = p->J;
+            p->J = J1 * gamma;
+            p->nbatch = nb1 * gamma;
+            p->nround = nr1 * gamma;
+            p->nrows = p->nround * r1;
+            p->batch_job.resize((size_t)p->nbatch);
+            p->batch_file0.resize((size_t)p->nbatch);
+            p->batch_label.resize((size_t)p->nbatch * r);
+            p->round_member.resize((size_t)p->nround * r1);
+            p->round_batch.resize((size_t)p->nround * r1);
+            for (int g = 1; g < gamma; g++) {
+                for (int64_t b = 0; b < nb1; b++) {
+                    p->batch_job[g * nb1 + b] = p->batch_job[b] + g * J1;
+                    p->batch_file0[g * nb1 + b] = p->batch_file0[b];
+                    for (int s = 0; s < r; s++) p->batch_label[(g * nb1 + b) * r + s] = p->batch_label[b * r + s];
+                }
+                for (int64_t i = 0; i < nr1 * r1; i++) {
+                    p->round_member[g * nr1 * r1 + i] = p->round_member[i];
+                    p->round_batch[g * nr1 * r1 + i] = p->round_batch[i] + (int32_t)(g * nb1);
                 }
             }
         }

@@ -79,7 +79,7 @@ struct ccdc_plan_s {
 namespace ccdc {
 
 // Host-side construction; both return a ccdc_status.
-int build_plan(int K, int r, int Q, int N, bool paper_jobs, ccdc_plan_t **out);
+int build_plan(int K, int r, int Q, int N, bool paper_jobs, int gamma, ccdc_plan_t **out);
 int build_compression_plan(int K, int r, int Q, int N, ccdc_plan_t **out);
 int bind_plan(ccdc_plan_t *p, int64_t T, int mode);
 

@@ -67,13 +67,13 @@ def assert_close(got, want, mode, name):
         assert err <= F32_TOL * max(scale, 1e-300), f"{name}: err {err:.3e} scale {scale:.3e}"
 
 
-def run_case(torch, L, K, r, Q, N, T, mode, jobs=False, seed=1, sigma=1.0):
-    op = O.build_plan(K, r, Q, N, "paper" if jobs else "single")
+def run_case(torch, L, K, r, Q, N, T, mode, jobs=False, seed=1, sigma=1.0, gamma=1):
+    op = O.build_plan(K, r, Q, N, "paper" if jobs else "single", gamma=gamma)
     Vh = generate_numpy(op.J, N, Q, T, seed, "u32" if mode == "u32" else "f32", sigma)
     ref = oracle_run(op, T, Vh, mode)
     ref_phi = O.direct(op, T, Vh)
 
-    plan = L.Plan(K, r, Q, N, jobs=jobs).bind(T, mode).upload()
+    plan = L.Plan(K, r, Q, N, jobs=jobs, gamma=gamma).bind(T, mode).upload()
     sh = plan.shapes()
     V = to_dev(torch, Vh)
     poison = -1 if mode == "u32" else float("nan")
@@ -193,6 +193,13 @@ def test_random_shapes(torch, L, seed):
     K, r, Q, N, T, jobs = random_shape(rng)
     mode = ["u32", "f32", "h32"][seed % 3]
     run_case(torch, L, K, r, Q, N, T, mode, jobs=jobs, seed=seed)
+
+
+@pytest.mark.parametrize("K,r,Q,N,T,gamma", [(4, 2, 4, 6, 512, 2), (5, 2, 10, 6, 258, 3), (4, 3, 4, 8, 40, 5)])
+@pytest.mark.parametrize("mode", ["u32", "f32", "h32"])
+def test_repeated_jobs_schedule(torch, L, K, r, Q, N, T, gamma, mode):
+    """J = gamma*C(K, r+1) jobs: the J-job scheme repeated on consecutive blocks of jobs (Sec. IV)."""
+    run_case(torch, L, K, r, Q, N, T, mode, jobs=True, seed=gamma, gamma=gamma)
 
 
 def test_unaligned_pointers_take_the_scalar_path(torch, L):

@@ -121,6 +121,24 @@ def test_node_rows_list_what_each_node_sends(lib, jobs):
     cp.close()
 
 
+def test_repeated_jobs_plan_equals_the_oracles(lib):
+    for (K, r, gamma) in [(4, 2, 2), (5, 2, 3), (4, 3, 4), (6, 1, 2)]:
+        N = (r + 1) * max(1, -(-K // (r + 1)))
+        p = B.ccdc_plan_jobs_repeated(K, r, 2 * K, N, gamma)
+        o = O.build_plan(K, r, 2 * K, N, "paper", gamma=gamma)
+        assert (p.J, p.n_batch, p.n_round) == (o.J, o.n_batch, o.n_round)
+        for name, tab in p.tables().items():
+            assert np.array_equal(tab, getattr(o, name)), (K, r, gamma, name)
+        p.bind(12, "u32")
+        assert p.scheduled_elems == O.scheduled_elems(o, 12)
+        assert tuple(p.shapes()["V"]) == (o.J, N, 2 * K, 12)
+        p.close()
+    h = C.c_void_p()
+    assert lib.ccdc_plan_jobs_repeated(4, 2, 4, 6, 0, C.byref(h)) == B.EINVAL and not h.value
+    assert lib.ccdc_plan_jobs_repeated(4, 2, 4, 6, 2, None) == B.EINVAL
+    assert lib.ccdc_plan_jobs_repeated(20, 9, 20, 20, 1 << 20, C.byref(h)) in (B.ESIZE, B.EINVAL)
+
+
 def test_workload_plans(lib):
     from workloads import CONFIGS
     for w in CONFIGS.values():
