@@ -139,6 +139,31 @@ def test_repeated_jobs_plan_equals_the_oracles(lib):
     assert lib.ccdc_plan_jobs_repeated(20, 9, 20, 20, 1 << 20, C.byref(h)) in (B.ESIZE, B.EINVAL)
 
 
+@pytest.mark.parametrize("K,r,jobs", [(40, 3, False), (30, 2, True), (64, 2, False)])
+def test_large_plans(lib, K, r, jobs):
+    """Tables of plans with 10^4 to 10^5 rounds: equal to the oracle's, every (node, batch it
+    does not store) served exactly once, every node in the same number of rounds."""
+    from math import comb
+    N = (r + 1) * 10 if jobs else comb(K, r)
+    p = B.Plan(K, r, K, N, jobs=jobs)
+    o = O.build_plan(K, r, K, N, "paper" if jobs else "single")
+    t = p.tables()
+    for name, tab in t.items():
+        assert np.array_equal(tab, getattr(o, name)), name
+    member, batch = t["round_member"].reshape(-1).astype(np.int64), t["round_batch"].reshape(-1).astype(np.int64)
+    pairs = member * p.n_batch + batch
+    assert np.unique(pairs).size == pairs.size                       # no batch twice to the same node
+    stores = np.zeros((K, p.n_batch), dtype=bool)
+    stores[t["batch_label"].reshape(-1), np.repeat(np.arange(p.n_batch), r)] = True
+    assert not stores[member, batch].any()                           # never a batch the node already stores
+    assert pairs.size == (~stores).sum()                             # and every missing one is served
+    assert (np.bincount(member, minlength=K) == pairs.size // K).all()
+    rows = p.node_rows()
+    assert np.array_equal(np.sort(rows.reshape(-1)), np.arange(pairs.size))
+    assert (member[rows] == np.arange(K)[:, None]).all()
+    p.close()
+
+
 def test_workload_plans(lib):
     from workloads import CONFIGS
     for w in CONFIGS.values():
