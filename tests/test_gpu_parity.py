@@ -172,6 +172,14 @@ def test_edge_shapes(torch, L, K, r, Q, N, T, jobs, mode):
     run_case(torch, L, K, r, Q, N, T, mode, jobs=jobs, seed=K * 10 + r)
 
 
+@pytest.mark.parametrize("K,r,N,T", [(40, 3, 9880, 64),      # 91 390 rounds, K*r = 120: one-element packs in the one-pass kernel
+                                     (64, 2, 2016, 128),     # 64 nodes, K*r = 128
+                                     (24, 5, 42504, 24)])    # r = 5 at 24 nodes: 134 596 rounds of 6 members
+@pytest.mark.parametrize("mode", ["u32", "f32"])
+def test_many_nodes(torch, L, K, r, N, T, mode):
+    run_case(torch, L, K, r, K, N, T, mode, seed=K)
+
+
 def random_shape(rng):
     """A valid (K, r, Q, N, T, jobs) drawn over the whole parameter space at small sizes."""
     from math import comb
