@@ -416,7 +416,13 @@ int bind_plan(ccdc_plan_t *p, int64_t T, int mode)
         int64_t pipe_cap = 1, local_rows = 0;
         std::vector<int64_t> loc;
         if (pipe_ok) {
-            if (T % 4 == 0 && (int64_t)p->K * r * 16 * kPipeLanes <= kPipeGoodLds) pipe_vec = 4;
+            // Small inputs are bound by how many wavefronts share the rounds: four-element
+            // packs only while six of them fit on a compute unit.  Large inputs are bound
+            // by the memory system, which is served better by wide accesses from three
+            // wavefronts than by narrow ones from six (both measured).
+            const bool large = v_elems * 4.0 >= (double)kPipeLargeInput;
+            const int64_t lds4 = large ? kPipeGoodLdsHalf : kPipeGoodLds;
+            if (T % 4 == 0 && (int64_t)p->K * r * 16 * kPipeLanes <= lds4) pipe_vec = 4;
             else if (T % 2 == 0 && (int64_t)p->K * r * 8 * kPipeLanes <= kPipeGoodLdsHalf) pipe_vec = 2;
             // chunk partials are written and read once more: keep them under ~1/4 of |V|
             const double v = (double)p->N * p->Q * (double)T, kw = (double)p->K * (double)W;

@@ -87,9 +87,9 @@ int bind_plan(ccdc_plan_t *p, int64_t T, int mode);
 constexpr int kPipeLanes = 64;                 // one wavefront per workgroup
 constexpr int kPipeMaxLds = 64 * 1024;         // bytes of LDS one workgroup may take
 // LDS a wavefront may take for its running outputs before a narrower pack is
-// preferred (measured): 16-byte packs only while >= 6 wavefronts fit on a
-// compute unit, 8-byte packs down to 3 wavefronts (4-byte accesses cost more
-// than the lost occupancy).
+// preferred (measured): four-element packs only while >= 6 wavefronts fit on a
+// compute unit, unless the input is large, then down to 3 wavefronts like
+// two-element packs (narrow accesses cost more than the lost occupancy).
 #ifndef CCDC_PIPE_GOOD_LDS
 #define CCDC_PIPE_GOOD_LDS (26 * 1024)
 #endif
@@ -98,6 +98,7 @@ constexpr int kPipeMaxLds = 64 * 1024;         // bytes of LDS one workgroup may
 #endif
 constexpr int kPipeGoodLds = CCDC_PIPE_GOOD_LDS;
 constexpr int kPipeGoodLdsHalf = CCDC_PIPE_GOOD_LDS_HALF;
+constexpr int64_t kPipeLargeInput = 256LL << 20;   // bytes of V (at 4 bytes an element) from which an input counts as large
 constexpr int kPipeMaxR1 = 6;                  // r+1 the kernel is unrolled for
 
 // Rank of sender a's label among the members other than b.
