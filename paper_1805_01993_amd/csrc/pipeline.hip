@@ -63,14 +63,17 @@ __global__ __launch_bounds__(ccdc::kPipeLanes) void k_pipeline(
     extern __shared__ __align__(16) unsigned char smem[];
     Q *acc = reinterpret_cast<Q *>(smem) + threadIdx.x;      // slot i of this lane: acc[i * LANES]
 
-    // Workgroups are handed to the 8 XCDs round-robin.  Renumber them so that each
-    // XCD gets a contiguous range of (chunk, tile) pairs: the tiles of one chunk
-    // (adjacent pieces of the same rows, the same table entries) then run next to
-    // each other in time behind one L2.
+    // Workgroups are handed to the 8 XCDs round-robin.  When the rounds are cut
+    // into chunks, renumber them so that each XCD gets a contiguous range of
+    // (chunk, tile) pairs: the tiles of one chunk (adjacent pieces of the same
+    // rows, the same table entries) then run next to each other in time behind one
+    // L2.  With a single chunk the hardware order is kept: all XCDs then sweep the
+    // same window of every row together (measured: 2 % either way).
     constexpr uint32_t XCDS = 8;
     const uint32_t nb = gridDim.x, q = nb / XCDS, rem = nb % XCDS;
     const uint32_t xcd = blockIdx.x % XCDS, j = blockIdx.x / XCDS;
-    const uint32_t logical = (xcd < rem ? xcd * (q + 1) : rem * (q + 1) + (xcd - rem) * q) + j;
+    const uint32_t logical =
+        chunks > 1 ? (xcd < rem ? xcd * (q + 1) : rem * (q + 1) + (xcd - rem) * q) + j : blockIdx.x;
     const uint32_t tile = logical % tiles, chunk = logical / tiles;
     const uint32_t x = tile * LANES + threadIdx.x;
     if (x >= Lv) return;
