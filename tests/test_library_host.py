@@ -164,6 +164,32 @@ def test_large_plans(lib, K, r, jobs):
     p.close()
 
 
+def test_random_plans_equal_the_oracles(lib):
+    """Seeded random parameters over K <= 12, every schedule: tables, segment split and
+    scheduled traffic of the library equal the oracle's."""
+    from math import comb
+    rng = np.random.default_rng(7)
+    for _ in range(80):
+        K = int(rng.integers(2, 13))
+        r = int(rng.integers(1, K))
+        jobs = bool(rng.integers(0, 2)) and comb(K, r + 1) * (K - r) <= 4000
+        gamma = int(rng.integers(1, 4)) if jobs else 1
+        c = int(rng.integers(1, 4))
+        nb = (r + 1) if jobs else comb(K, r)
+        m = int(rng.integers(1, 4))
+        while m * nb < K:
+            m += 1
+        T = int(rng.integers(1, 300))
+        p = B.Plan(K, r, c * K, m * nb, jobs=jobs, gamma=gamma)
+        o = O.build_plan(K, r, c * K, m * nb, "paper" if jobs else "single", gamma=gamma)
+        for name, tab in p.tables().items():
+            assert np.array_equal(tab, getattr(o, name)), (K, r, jobs, gamma, name)
+        p.bind(T, "f32")
+        assert p.seg_len == O.segment_len(c * T, r) and p.scheduled_elems == O.scheduled_elems(o, T)
+        assert all(tuple(p.shapes()[k]) == tuple(v) for k, v in o.shapes(T).items())
+        p.close()
+
+
 def test_workload_plans(lib):
     from workloads import CONFIGS
     for w in CONFIGS.values():
