@@ -37,8 +37,12 @@
  * written to an output on error and the library never aborts or throws.
  * Stage calls only enqueue kernels on `stream` (a hipStream_t passed as
  * void*, NULL = the default stream) and allocate nothing; execution errors
- * surface at the caller's next synchronisation.  A plan may be used from one
- * stream at a time (its reduction workspace is shared between calls).
+ * surface at the caller's next synchronisation.  The calls that keep partial
+ * sums in the plan's workspace (ccdc_reduce, ccdc_pipeline_fused,
+ * ccdc_node_decode_reduce) are put in order by the library when they come on
+ * different streams or host threads: the later call's stream waits for the
+ * earlier call's kernels.  A stream under graph capture is not ordered this way;
+ * replay such a graph apart from other work on the same plan.
  */
 #ifndef CCDC_H
 #define CCDC_H

@@ -247,7 +247,7 @@ void release_device(ccdc_plan_t *p)
 {
     if (!p) return;
     if (p->uploaded || p->d_src_off || p->d_red_ptr || p->d_red_row || p->d_red_out || p->d_loc_row || p->d_member ||
-        p->d_row_files || p->d_node_rows || p->d_workspace) {
+        p->d_row_files || p->d_node_rows || p->d_workspace || p->ws_event) {
         int cur = -1;
         const bool sw = hipGetDevice(&cur) == hipSuccess && p->device >= 0 && cur != p->device &&
                         hipSetDevice(p->device) == hipSuccess;
@@ -260,6 +260,7 @@ void release_device(ccdc_plan_t *p)
         (void)hipFree(p->d_row_files);
         (void)hipFree(p->d_node_rows);
         (void)hipFree(p->d_workspace);
+        if (p->ws_event) (void)hipEventDestroy((hipEvent_t)p->ws_event);
         if (sw) (void)hipSetDevice(cur);
     }
     p->d_src_off = p->d_red_ptr = p->d_red_row = p->d_red_out = p->d_loc_row = nullptr;
@@ -267,8 +268,10 @@ void release_device(ccdc_plan_t *p)
     p->d_row_files = nullptr;
     p->d_node_rows = nullptr;
     p->d_workspace = nullptr;
-    p->pipe_kernel = nullptr;
-    p->pipe_chunks = 0;
+    p->pipe_chunks[0] = p->pipe_chunks[1] = p->pipe_chunks[2] = 0;
+    p->ws_event = nullptr;
+    p->ws_stream = nullptr;
+    p->ws_used = false;
     p->uploaded = false;
     p->device = -1;
 }
@@ -372,6 +375,7 @@ int run_reduce(const ccdc_plan_t *p, const void *V, const void *D, void *Phi, hi
     const uint64_t blocks = (uint64_t)p->nout * split * tiles;
     const int64_t chunk_stride = (int64_t)p->J * p->Q * p->T;
     using Acc = typename A::acc;
+    WorkspaceOrder order(p, st, split > 1);
     k_reduce_rows<A, VEC><<<(uint32_t)blocks, kBlock, 0, st>>>((const E *)V, (const E *)D, (E *)Phi,
                                                                 (Acc *)p->d_workspace, p->d_red_ptr, p->d_red_row,
                                                                 p->d_red_out, Wv, tiles, split, chunk_stride);
@@ -443,10 +447,19 @@ int ccdc_plan_upload(ccdc_plan_t *plan)
         (void)hipGetLastError();
         rc = CCDC_ENOMEM;
     }
+    if (rc == CCDC_OK && plan->workspace_bytes > 0) {
+        hipEvent_t ev = nullptr;
+        if (hipEventCreateWithFlags(&ev, hipEventDisableTiming) != hipSuccess) {
+            (void)hipGetLastError();
+            rc = CCDC_EHIP;
+        }
+        plan->ws_event = ev;
+    }
     if (rc != CCDC_OK) {
         release_device(plan);
         return rc;
     }
+    ccdc::pipeline_prepare(plan);                 // launch geometry of the one-pass kernel on this device
     plan->uploaded = true;
     return CCDC_OK;
 }

@@ -294,6 +294,51 @@ inline int launched()
     return hipGetLastError() == hipSuccess ? CCDC_OK : CCDC_EHIP;
 }
 
+// The plan's workspace holds partial sums between the two kernels of one call.
+// Calls that use it are put in order also when they come on different streams:
+// each records the plan's event once its kernels are enqueued, and a call on
+// another stream first makes its stream wait for that event.  Host threads
+// take turns through the plan's mutex.  A stream under graph capture is left
+// alone (an event recorded outside a capture cannot be waited for inside one):
+// whoever replays the graph keeps it apart from other users of the plan.
+class WorkspaceOrder {
+public:
+    WorkspaceOrder(const ccdc_plan_t *p, hipStream_t st, bool uses_workspace)
+        : p_(p), st_(st), on_(uses_workspace && p->ws_event != nullptr)
+    {
+        if (!on_) return;
+        p_->ws_mutex.lock();
+        hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+        if (hipStreamIsCapturing(st_, &cs) != hipSuccess || cs != hipStreamCaptureStatusNone) {
+            (void)hipGetLastError();
+            p_->ws_mutex.unlock();
+            on_ = false;
+            return;
+        }
+        if (p_->ws_used && p_->ws_stream != (void *)st_ &&
+            hipStreamWaitEvent(st_, (hipEvent_t)p_->ws_event, 0) != hipSuccess)
+            (void)hipGetLastError();
+    }
+    ~WorkspaceOrder()
+    {
+        if (!on_) return;
+        if (hipEventRecord((hipEvent_t)p_->ws_event, st_) == hipSuccess) {
+            p_->ws_used = true;
+            p_->ws_stream = (void *)st_;
+        } else {
+            (void)hipGetLastError();
+        }
+        p_->ws_mutex.unlock();
+    }
+    WorkspaceOrder(const WorkspaceOrder &) = delete;
+    WorkspaceOrder &operator=(const WorkspaceOrder &) = delete;
+
+private:
+    const ccdc_plan_t *p_;
+    hipStream_t st_;
+    bool on_;
+};
+
 }  // namespace ccdc
 
 // Dispatch on (payload mode, pack width): evaluates CALL with the algebra as type A and the

@@ -151,6 +151,7 @@ int run_node_decode_reduce(const ccdc_plan_t *p, int node, const void *V, const 
     const uint32_t o_first = node < 0 ? 0u : (uint32_t)node, o_step = node < 0 ? 1u : (uint32_t)p->K;
     const int64_t chunk_stride = (int64_t)p->J * p->Q * p->T;
     const uint64_t blocks = (uint64_t)count * split * tiles;
+    WorkspaceOrder order(p, st, split > 1);
     k_node_decode_reduce<A, VEC><<<(uint32_t)blocks, kBlock, 0, st>>>(
         (const E *)V, (const E *)X, (E *)Phi, (Acc *)p->d_workspace, p->d_red_ptr, p->d_red_row, p->d_red_out,
         p->d_src_off, p->r + 1, Lv, Wv, p->W, p->m, (int64_t)p->Q * p->T, tiles, split, chunk_stride, o_first, o_step);

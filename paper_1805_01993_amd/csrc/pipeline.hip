@@ -1,4 +1,6 @@
 // One-pass pipeline kernel (combine + encode + decode + reduce) and its entry point.
+#include <type_traits>
+
 #include "common.hpp"
 
 namespace {
@@ -250,77 +252,104 @@ __global__ __launch_bounds__(ccdc::kPipeLanes) void k_pipeline(
     }
 }
 
-// Round chunks for this launch: when there are fewer column tiles than
-// wavefront slots on the device, cut the rounds so that the grid is one
-// resident wave of equally loaded workgroups (bounded by the workspace).
-template <class KernelT>
-int chunks_for(const ccdc_plan_t *p, KernelT kernel, uint32_t tiles, size_t lds)
+// Every k_pipeline<A, VEC, R1, *, *> has this signature.
+template <class A>
+using PipeKernel = void (*)(const typename A::elem *, typename A::elem *, typename A::elem *, typename A::acc *,
+                            const int64_t *, const int32_t *, const int64_t *, int, uint32_t, uint32_t, int, int64_t,
+                            uint32_t, uint32_t, uint32_t, uint32_t, int64_t);
+
+// The instantiation a plan runs: MULTI when a batch has several files, RAGGED
+// when the last segment is short or empty.  Null for an r the kernel is not
+// unrolled for.
+template <class A, int VEC>
+PipeKernel<A> pipeline_kernel(const ccdc_plan_t *p)
 {
-    const void *key = reinterpret_cast<const void *>(kernel);
-    if (p->pipe_kernel == key && p->pipe_chunks > 0) return p->pipe_chunks;
+    const bool ragged = p->ell * p->r != p->W;
+    auto of = [&](auto r1) -> PipeKernel<A> {
+        constexpr int R1 = decltype(r1)::value;
+        if (p->m > 1) return k_pipeline<A, VEC, R1, true, true>;
+        if (ragged) return k_pipeline<A, VEC, R1, false, true>;
+        return k_pipeline<A, VEC, R1, false, false>;
+    };
+    switch (p->r + 1) {
+    case 2: return of(std::integral_constant<int, 2>());
+    case 3: return of(std::integral_constant<int, 3>());
+    case 4: return of(std::integral_constant<int, 4>());
+    case 5: return of(std::integral_constant<int, 5>());
+    case 6: return of(std::integral_constant<int, 6>());
+    default: return nullptr;
+    }
+}
+
+template <int VEC>
+size_t pipeline_lds(const ccdc_plan_t *p)
+{
+    return (size_t)p->K * p->r * ccdc::kPipeLanes * VEC * sizeof(float);     // every algebra sums in 4 bytes
+}
+
+template <int VEC>
+uint32_t pipeline_tiles(const ccdc_plan_t *p)
+{
+    return cdiv((uint64_t)(p->ell / VEC), ccdc::kPipeLanes);
+}
+
+// Round chunks for a launch with VEC-element packs: when there are fewer column
+// tiles than wavefront slots on the device, the rounds are cut so that the grid
+// is one resident wave of equally loaded workgroups (bounded by the workspace).
+template <class A, int VEC>
+int chunks_for(const ccdc_plan_t *p)
+{
+    PipeKernel<A> kernel = pipeline_kernel<A, VEC>(p);
+    if (!kernel || p->ell % VEC != 0 || p->T % VEC != 0) return 1;
     int per_cu = 0, cus = 0, dev = 0;
     if (hipGetDevice(&dev) != hipSuccess ||
         hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
-        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, ccdc::kPipeLanes, lds) != hipSuccess ||
+        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, ccdc::kPipeLanes, pipeline_lds<VEC>(p)) !=
+            hipSuccess ||
         per_cu < 1 || cus < 1) {
         (void)hipGetLastError();
         return 1;
     }
-    const int64_t slots = (int64_t)per_cu * cus;
-    int64_t chunks = slots / tiles;
+    int64_t chunks = (int64_t)per_cu * cus / pipeline_tiles<VEC>(p);
     if (chunks < 1) chunks = 1;
     if (chunks > p->pipe_max_chunks) chunks = p->pipe_max_chunks;
-    p->pipe_kernel = key;
-    p->pipe_chunks = (int)chunks;
     return (int)chunks;
 }
 
-template <class A, int VEC, int R1>
-int launch_pipeline(const ccdc_plan_t *p, const void *V, void *X, void *Phi, hipStream_t st, int *chunks_out)
+template <class A>
+void prepare(ccdc_plan_t *p)
 {
-    using E = typename A::elem;
-    const uint32_t Wv = (uint32_t)(p->W / VEC), Lv = (uint32_t)(p->ell / VEC);
-    const uint32_t tiles = cdiv(Lv, ccdc::kPipeLanes);
-    const size_t lds = (size_t)p->K * p->r * ccdc::kPipeLanes * VEC * sizeof(typename A::acc);
-    auto go = [&](auto kernel) {
-        const int chunks = chunks_for(p, kernel, tiles, lds);
-        kernel<<<tiles * (uint32_t)chunks, ccdc::kPipeLanes, lds, st>>>(
-            (const E *)V, (E *)X, (E *)Phi, (typename A::acc *)p->d_workspace, p->d_src_off, p->d_member, p->d_loc_row,
-            p->K, Lv, Wv, p->m,
-            (int64_t)p->Q * p->T, (uint32_t)p->nround, tiles, (uint32_t)chunks,
-            (uint32_t)(p->K * p->pipe_local_rows), (int64_t)p->K * p->W);
-        *chunks_out = chunks;
-    };
-    const bool ragged = p->ell * p->r != p->W;
-    if (p->m > 1) go(k_pipeline<A, VEC, R1, true, true>);
-    else if (ragged) go(k_pipeline<A, VEC, R1, false, true>);
-    else go(k_pipeline<A, VEC, R1, false, false>);
-    return launched();
+    p->pipe_chunks[0] = chunks_for<A, 1>(p);
+    p->pipe_chunks[1] = p->pipe_vec >= 2 ? chunks_for<A, 2>(p) : 1;
+    p->pipe_chunks[2] = p->pipe_vec >= 4 ? chunks_for<A, 4>(p) : 1;
 }
 
+// One launch of the pass with `chunks` round chunks; partial outputs of the
+// chunks go to `part` (chunks * K * W sums) and k_reduce_final adds them.
 template <class A, int VEC>
-int run_pipeline(const ccdc_plan_t *p, const void *V, void *X, void *Phi, bool wide_final, hipStream_t st)
+int run_pipeline(const ccdc_plan_t *p, const void *V, void *X, void *Phi, void *part, int chunks, bool wide_final,
+                 hipStream_t st)
 {
     using E = typename A::elem;
     using Acc = typename A::acc;
-    int chunks = 1, rc;
-    switch (p->r + 1) {
-    case 2: rc = launch_pipeline<A, VEC, 2>(p, V, X, Phi, st, &chunks); break;
-    case 3: rc = launch_pipeline<A, VEC, 3>(p, V, X, Phi, st, &chunks); break;
-    case 4: rc = launch_pipeline<A, VEC, 4>(p, V, X, Phi, st, &chunks); break;
-    case 5: rc = launch_pipeline<A, VEC, 5>(p, V, X, Phi, st, &chunks); break;
-    case 6: rc = launch_pipeline<A, VEC, 6>(p, V, X, Phi, st, &chunks); break;
-    default: return CCDC_ESIZE;
-    }
+    PipeKernel<A> kernel = pipeline_kernel<A, VEC>(p);
+    if (!kernel) return CCDC_ESIZE;
+    const uint32_t Wv = (uint32_t)(p->W / VEC), Lv = (uint32_t)(p->ell / VEC);
+    const uint32_t tiles = pipeline_tiles<VEC>(p);
+    kernel<<<tiles * (uint32_t)chunks, ccdc::kPipeLanes, pipeline_lds<VEC>(p), st>>>(
+        (const E *)V, (E *)X, (E *)Phi, (Acc *)part, p->d_src_off, p->d_member, p->d_loc_row, p->K, Lv, Wv, p->m,
+        (int64_t)p->Q * p->T, (uint32_t)p->nround, tiles, (uint32_t)chunks, (uint32_t)(p->K * p->pipe_local_rows),
+        (int64_t)p->K * p->W);
+    int rc = launched();
     if (rc != CCDC_OK || chunks == 1) return rc;
     const int64_t n = (int64_t)p->K * p->W;
     if (wide_final) {
         const int G = reduce_final_groups(n / 4, chunks);
-        k_reduce_final<A, 4><<<cdiv(n / 4, kBlock / G), kBlock, 0, st>>>((const Acc *)p->d_workspace, (E *)Phi, chunks,
-                                                                          n / 4, (uint32_t)(n / 4), G);
+        k_reduce_final<A, 4><<<cdiv(n / 4, kBlock / G), kBlock, 0, st>>>((const Acc *)part, (E *)Phi, chunks, n / 4,
+                                                                          (uint32_t)(n / 4), G);
     } else {
         const int G = reduce_final_groups(n, chunks);
-        k_reduce_final<A, 1><<<cdiv(n, kBlock / G), kBlock, 0, st>>>((const Acc *)p->d_workspace, (E *)Phi, chunks, n,
+        k_reduce_final<A, 1><<<cdiv(n, kBlock / G), kBlock, 0, st>>>((const Acc *)part, (E *)Phi, chunks, n,
                                                                       (uint32_t)n, G);
     }
     return launched();
@@ -328,9 +357,14 @@ int run_pipeline(const ccdc_plan_t *p, const void *V, void *X, void *Phi, bool w
 
 }  // namespace
 
-extern "C" {
+namespace ccdc {
 
-int ccdc_pipeline_fused(const ccdc_plan_t *plan, const void *V, void *X, void *Phi, void *stream)
+// ccdc_pipeline_fused: checks, pack width, dispatch on the algebra.  The partial
+// outputs of round chunks go to the plan's workspace, or, when the caller brings
+// a buffer (own_part, of own_part_bytes bytes), to that one; a launch whose
+// chunks do not fit a brought buffer is refused.
+int pipeline_entry(const ccdc_plan_t *plan, const void *V, void *X, void *Phi, void *stream, void *own_part,
+                   size_t own_part_bytes)
 {
     int rc = ready(plan), vec_any = 1;
     if (rc != CCDC_OK) return rc;
@@ -343,30 +377,61 @@ int ccdc_pipeline_fused(const ccdc_plan_t *plan, const void *V, void *X, void *P
     int vec = plan->pipe_vec;
     while (vec > 1 && !(aligned(V, eb * vec) && aligned(X, eb * vec) && aligned(Phi, eb * vec))) vec /= 2;
     const bool wide_final = vec_any >= 4;            // Phi can be written four elements at a time
+    const int chunks = plan->pipe_chunks[vec == 4 ? 2 : (vec == 2 ? 1 : 0)];
+    if (chunks < 1) return CCDC_ESTATE;
+    void *part = plan->d_workspace;
+    if (own_part) {
+        if (chunks > 1 && (uint64_t)chunks * (uint64_t)plan->K * (uint64_t)plan->W * 4u > (uint64_t)own_part_bytes)
+            return CCDC_ESIZE;
+        part = own_part;
+    }
     hipStream_t st = (hipStream_t)stream;
+    WorkspaceOrder order(plan, st, !own_part && chunks > 1);
     if (plan->mode == CCDC_F32_SUM) {
-        if (vec == 4) return run_pipeline<SumF32, 4>(plan, V, X, Phi, wide_final, st);
-        if (vec == 2) return run_pipeline<SumF32, 2>(plan, V, X, Phi, wide_final, st);
-        return run_pipeline<SumF32, 1>(plan, V, X, Phi, wide_final, st);
+        if (vec == 4) return run_pipeline<SumF32, 4>(plan, V, X, Phi, part, chunks, wide_final, st);
+        if (vec == 2) return run_pipeline<SumF32, 2>(plan, V, X, Phi, part, chunks, wide_final, st);
+        return run_pipeline<SumF32, 1>(plan, V, X, Phi, part, chunks, wide_final, st);
     }
     if (plan->mode == CCDC_F32_SUM_XOR) {
-        if (vec == 4) return run_pipeline<HybF32, 4>(plan, V, X, Phi, wide_final, st);
-        if (vec == 2) return run_pipeline<HybF32, 2>(plan, V, X, Phi, wide_final, st);
-        return run_pipeline<HybF32, 1>(plan, V, X, Phi, wide_final, st);
+        if (vec == 4) return run_pipeline<HybF32, 4>(plan, V, X, Phi, part, chunks, wide_final, st);
+        if (vec == 2) return run_pipeline<HybF32, 2>(plan, V, X, Phi, part, chunks, wide_final, st);
+        return run_pipeline<HybF32, 1>(plan, V, X, Phi, part, chunks, wide_final, st);
     }
     if (plan->mode == CCDC_BF16_SUM_XOR) {
-        if (vec == 4) return run_pipeline<HybBF16, 4>(plan, V, X, Phi, wide_final, st);
-        if (vec == 2) return run_pipeline<HybBF16, 2>(plan, V, X, Phi, wide_final, st);
-        return run_pipeline<HybBF16, 1>(plan, V, X, Phi, wide_final, st);
+        if (vec == 4) return run_pipeline<HybBF16, 4>(plan, V, X, Phi, part, chunks, wide_final, st);
+        if (vec == 2) return run_pipeline<HybBF16, 2>(plan, V, X, Phi, part, chunks, wide_final, st);
+        return run_pipeline<HybBF16, 1>(plan, V, X, Phi, part, chunks, wide_final, st);
     }
     if (plan->mode == CCDC_F16_SUM_XOR) {
-        if (vec == 4) return run_pipeline<HybF16, 4>(plan, V, X, Phi, wide_final, st);
-        if (vec == 2) return run_pipeline<HybF16, 2>(plan, V, X, Phi, wide_final, st);
-        return run_pipeline<HybF16, 1>(plan, V, X, Phi, wide_final, st);
+        if (vec == 4) return run_pipeline<HybF16, 4>(plan, V, X, Phi, part, chunks, wide_final, st);
+        if (vec == 2) return run_pipeline<HybF16, 2>(plan, V, X, Phi, part, chunks, wide_final, st);
+        return run_pipeline<HybF16, 1>(plan, V, X, Phi, part, chunks, wide_final, st);
     }
-    if (vec == 4) return run_pipeline<XorU32, 4>(plan, V, X, Phi, wide_final, st);
-    if (vec == 2) return run_pipeline<XorU32, 2>(plan, V, X, Phi, wide_final, st);
-    return run_pipeline<XorU32, 1>(plan, V, X, Phi, wide_final, st);
+    if (vec == 4) return run_pipeline<XorU32, 4>(plan, V, X, Phi, part, chunks, wide_final, st);
+    if (vec == 2) return run_pipeline<XorU32, 2>(plan, V, X, Phi, part, chunks, wide_final, st);
+    return run_pipeline<XorU32, 1>(plan, V, X, Phi, part, chunks, wide_final, st);
+}
+
+void pipeline_prepare(ccdc_plan_t *p)
+{
+    p->pipe_chunks[0] = p->pipe_chunks[1] = p->pipe_chunks[2] = 1;
+    if (!p->pipe_ok) return;
+    switch (p->mode) {
+    case CCDC_F32_SUM: prepare<SumF32>(p); break;
+    case CCDC_F32_SUM_XOR: prepare<HybF32>(p); break;
+    case CCDC_BF16_SUM_XOR: prepare<HybBF16>(p); break;
+    case CCDC_F16_SUM_XOR: prepare<HybF16>(p); break;
+    default: prepare<XorU32>(p); break;
+    }
+}
+
+}  // namespace ccdc
+
+extern "C" {
+
+int ccdc_pipeline_fused(const ccdc_plan_t *plan, const void *V, void *X, void *Phi, void *stream)
+{
+    return ccdc::pipeline_entry(plan, V, X, Phi, stream, nullptr, 0);
 }
 
 }  // extern "C"

@@ -4,6 +4,7 @@
 
 #include <cstddef>
 #include <cstdint>
+#include <mutex>
 #include <vector>
 
 #include "ccdc.h"
@@ -70,10 +71,16 @@ struct ccdc_plan_s {
     int32_t *d_node_rows = nullptr;
     void *d_workspace = nullptr;
 
-    // launch geometry of the one-pass kernel last used on this device (an occupancy
-    // query answers it; remembered so that repeated calls do not ask again)
-    mutable const void *pipe_kernel = nullptr;
-    mutable int pipe_chunks = 0;
+    // round chunks of the one-pass kernel on this device for packs of 1, 2 and 4
+    // elements (index log2 of the width), from an occupancy query at upload time
+    int pipe_chunks[3] = {0, 0, 0};
+
+    // Order of the calls that use the workspace, across streams: the last such call
+    // recorded ws_event (a hipEvent_t made by ccdc_plan_upload) on ws_stream.
+    mutable std::mutex ws_mutex;
+    mutable void *ws_event = nullptr;
+    mutable void *ws_stream = nullptr;
+    mutable bool ws_used = false;
 };
 
 namespace ccdc {
@@ -100,6 +107,14 @@ constexpr int kPipeGoodLds = CCDC_PIPE_GOOD_LDS;
 constexpr int kPipeGoodLdsHalf = CCDC_PIPE_GOOD_LDS_HALF;
 constexpr int64_t kPipeLargeInput = 256LL << 20;   // bytes of V (at 4 bytes an element) from which an input counts as large
 constexpr int kPipeMaxR1 = 6;                  // r+1 the kernel is unrolled for
+
+// One-pass pipeline (pipeline.hip): fills p->pipe_chunks for the current device.
+void pipeline_prepare(ccdc_plan_t *p);
+// Body of ccdc_pipeline_fused.  own_part = null: partial outputs of round chunks go
+// to the plan's workspace; else to the caller's buffer of own_part_bytes bytes
+// (CCDC_ESIZE when they do not fit).
+int pipeline_entry(const ccdc_plan_t *plan, const void *V, void *X, void *Phi, void *stream, void *own_part,
+                   size_t own_part_bytes);
 
 // Rank of sender a's label among the members other than b.
 inline int label_rank(int a, int b) { return a - (a > b ? 1 : 0); }

@@ -264,6 +264,49 @@ def test_results_are_deterministic_and_on_the_given_stream(torch, L):
     plan.close()
 
 
+def test_one_plan_on_two_streams_is_put_in_order(torch, L):
+    """Two calls that both keep partial sums in the plan's workspace, issued back to back
+    on different streams with different inputs: the library orders them, so each gives
+    exactly what it gives alone."""
+    K, r, Q, N, T = 10, 3, 10, 120, 32768
+    plan = L.ccdc_plan(K, r, Q, N).bind(T, "f32").upload()
+    assert plan.workspace_bytes > 0
+    sh = plan.shapes()
+    Va = generate_torch(1, N, Q, T, 11, "f32", device="cuda")
+    Vb = generate_torch(1, N, Q, T, 12, "f32", device="cuda")
+    alone = []
+    for V in (Va, Vb):
+        X, Phi = dev_empty(torch, sh["X"], "f32", float("nan")), dev_empty(torch, sh["Phi"], "f32", float("nan"))
+        plan.pipeline_fused(V, X, Phi)
+        torch.cuda.synchronize()
+        alone.append((X, Phi))
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    for rep in range(3):
+        outs = [(dev_empty(torch, sh["X"], "f32", float("nan")), dev_empty(torch, sh["Phi"], "f32", float("nan")))
+                for _ in range(4)]
+        torch.cuda.synchronize()
+        for i, (X, Phi) in enumerate(outs):          # a, b, a, b with no host wait in between
+            plan.pipeline_fused((Va, Vb)[i % 2], X, Phi, stream=(sa, sb)[i % 2])
+        torch.cuda.synchronize()
+        for i, (X, Phi) in enumerate(outs):
+            assert torch.equal(X, alone[i % 2][0]), (rep, i)
+            assert torch.equal(Phi, alone[i % 2][1]), (rep, i)
+    # the separate reduction and the node-local reduction use the same workspace
+    D = dev_empty(torch, sh["D"], "f32", float("nan"))
+    X = dev_empty(torch, sh["X"], "f32", float("nan"))
+    plan.shuffle_fused(Va, X, D)
+    P0, P1, P2 = (dev_empty(torch, sh["Phi"], "f32", float("nan")) for _ in range(3))
+    plan.reduce(Va, D, P0)
+    torch.cuda.synchronize()
+    plan.reduce(Va, D, P1, stream=sa)
+    plan.node_decode_reduce(-1, Va, X, P2, stream=sb)
+    plan.reduce(Va, D, P1, stream=sa)
+    torch.cuda.synchronize()
+    assert torch.equal(P0, P1)
+    assert_close(to_host(P2, "f32"), to_host(P0, "f32").astype(np.float64), "f32", "node-local Phi")
+    plan.close()
+
+
 def test_rebinding_a_plan(torch, L):
     plan = L.ccdc_plan(4, 2, 4, 12)
     for T, mode in ((256, "f32"), (100, "u32"), (256, "u32")):
