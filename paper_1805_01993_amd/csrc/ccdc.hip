@@ -78,7 +78,7 @@ __global__ __launch_bounds__(64) void k_combine_wave(const typename A::elem *__r
 
 // ------------------------------------------------------------------- encode
 // Sec. IV-B coded packet.  One work item = one pack of X[u][a]: the sum over
-// the other members b of segment label_rank(a,b) of Vbar[u][b] at the same
+// the other members b of segment segment_rank(a,b) of Vbar[u][b] at the same
 // in-segment position; positions past the end of a short segment add nothing.
 template <class A, int VEC>
 __global__ __launch_bounds__(kBlock) void k_encode(const typename A::elem *__restrict__ Vbar,
@@ -96,7 +96,7 @@ __global__ __launch_bounds__(kBlock) void k_encode(const typename A::elem *__res
     P acc = O::zero();
     for (int b = 0; b < r1; b++) {
         if (b == a) continue;
-        const uint32_t pos = label_rank(a, b) * Lv + x;
+        const uint32_t pos = segment_rank(a, b) * Lv + x;
         if (pos < Wv) acc = O::code(acc, rows[(size_t)b * Wv + pos]);
     }
     reinterpret_cast<P *>(X)[idx] = acc;
@@ -127,7 +127,7 @@ __global__ __launch_bounds__(kBlock) void k_decode(const typename A::elem *__res
     P acc = reinterpret_cast<const P *>(X)[((size_t)u * r1 + a) * Lv + x];
     for (int b2 = 0; b2 < r1; b2++) {
         if (b2 == a || b2 == b) continue;
-        const uint32_t pos = label_rank(a, b2) * Lv + x;
+        const uint32_t pos = segment_rank(a, b2) * Lv + x;
         if (pos < Wv) acc = O::uncode(acc, rows[(size_t)b2 * Wv + pos]);
     }
     reinterpret_cast<P *>(D)[idx] = acc;
@@ -159,7 +159,7 @@ __global__ __launch_bounds__(kBlock) void k_shuffle_fused(const typename A::elem
     const int64_t *src = src_off + (size_t)u * r1;
 
     auto combined = [&](int b) -> P {       // pack of Vbar[u][b] that sender a carries
-        const uint32_t pos = label_rank(a, b) * Lv + x;
+        const uint32_t pos = segment_rank(a, b) * Lv + x;
         if (pos >= Wv) return O::zero();
         const typename A::elem *s = V + src[b] + (int64_t)pos * VEC;
         typename O::Q acc = O::widen(load_stream<P>(s));
@@ -181,7 +181,7 @@ __global__ __launch_bounds__(kBlock) void k_shuffle_fused(const typename A::elem
 #pragma unroll
         for (int b = 0; b < R1; b++) {
             if (b == a) continue;
-            const uint32_t pos = label_rank(a, b) * Lv + x;
+            const uint32_t pos = segment_rank(a, b) * Lv + x;
             if (pos >= Wv) continue;
             P acc = coded;
 #pragma unroll
@@ -196,7 +196,7 @@ __global__ __launch_bounds__(kBlock) void k_shuffle_fused(const typename A::elem
         store_stream(reinterpret_cast<P *>(X) + idx, coded);
         for (int b = 0; b < r1; b++) {
             if (b == a) continue;
-            const uint32_t pos = label_rank(a, b) * Lv + x;
+            const uint32_t pos = segment_rank(a, b) * Lv + x;
             if (pos >= Wv) continue;
             P acc = coded;
             for (int b2 = 0; b2 < r1; b2++)

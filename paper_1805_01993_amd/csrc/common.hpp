@@ -208,7 +208,8 @@ __device__ __forceinline__ void store_stream(void *p, const P &v)
 
 constexpr int kBlock = 256;
 
-__device__ __forceinline__ int label_rank(int a, int b) { return a - (a > b ? 1 : 0); }
+// Which segment of packet b carries sender a's label: the rank of a among the members other than b.
+__device__ __forceinline__ int segment_rank(int a, int b) { return a - (a > b ? 1 : 0); }
 
 // Phi = sum over chunks of the per-chunk outputs part[split][chunk_packs].
 // A workgroup owns kBlock/G consecutive packs; its G thread groups each add

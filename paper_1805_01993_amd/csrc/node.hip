@@ -46,7 +46,7 @@ __global__ __launch_bounds__(kBlock) void k_node_encode(const typename A::elem *
     P coded = O::zero();
     for (int b = 0; b < r1; b++) {
         if (b == a) continue;
-        const uint32_t pos = label_rank(a, b) * Lv + x;
+        const uint32_t pos = segment_rank(a, b) * Lv + x;
         if (pos < Wv) coded = O::code(coded, combined_pack<A, VEC>(V, src[b], pos, m, file_stride));
     }
     store_stream(reinterpret_cast<P *>(X) + (size_t)i * Lv + x, coded);
@@ -96,7 +96,7 @@ __global__ __launch_bounds__(kBlock) void k_node_decode_reduce(
         P d = load_stream<P>(reinterpret_cast<const P *>(X) + ((size_t)u * r1 + a) * Lv + x);
         for (int b2 = 0; b2 < r1; b2++) {
             if (b2 == a || b2 == b) continue;
-            const uint32_t pos = label_rank(a, b2) * Lv + x;
+            const uint32_t pos = segment_rank(a, b2) * Lv + x;
             if (pos < Wv) d = O::uncode(d, combined_pack<A, VEC>(V, src[b2], pos, m, file_stride));
         }
         acc = O::accum(acc, d);
