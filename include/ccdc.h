@@ -219,6 +219,20 @@ int ccdc_shuffle_fused(const ccdc_plan_t *plan, const void *V, void *X, void *D,
  * use ccdc_shuffle_fused + ccdc_reduce there. */
 int ccdc_pipeline_fused(const ccdc_plan_t *plan, const void *V, void *X, void *Phi, void *stream);
 
+/* ccdc_pipeline_fused for callers that cannot have device memory allocated for
+ * them: code recorded into a HIP graph, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, same X bit for bit and the same Phi (same
+ * chunks, same summation order) as ccdc_pipeline_fused, but the partial outputs
+ * of the round chunks go to a fixed 64 MiB array in device memory that the
+ * library holds on every GPU it runs on, instead of the plan's workspace; the
+ * call itself allocates and frees nothing.  CCDC_ESIZE when the plan's chunks
+ * need more than 64 MiB (chunks * K * W * 4 bytes; a launch with a single chunk
+ * needs none and is never refused for its size); other errors as
+ * ccdc_pipeline_fused.  All calls on one GPU share the array: two of them that
+ * overlap in time (different streams, different plans) race; keep them on one
+ * stream or order them yourself. */
+int ccdc_pipeline_fused_noalloc(const ccdc_plan_t *plan, const void *V, void *X, void *Phi, void *stream);
+
 /*
  * The node-local form of the path: what ONE node of the cluster does in the
  * shuffle, from nothing but the files it stores and the coded packets it

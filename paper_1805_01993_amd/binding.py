@@ -30,7 +30,8 @@ ELEM_BYTES = {F32_SUM: 4, U32_XOR: 4, F32_SUM_XOR: 4, BF16_SUM_XOR: 2, F16_SUM_X
 EXPORTS = [
     "ccdc_plan", "ccdc_plan_jobs", "ccdc_plan_jobs_repeated", "ccdc_plan_compression", "ccdc_plan_destroy", "ccdc_plan_bind", "ccdc_plan_upload",
     "ccdc_plan_query", "ccdc_strerror", "ccdc_combine", "ccdc_encode", "ccdc_decode", "ccdc_reduce",
-    "ccdc_shuffle_fused", "ccdc_pipeline_fused", "ccdc_node_encode", "ccdc_node_decode_reduce",
+    "ccdc_shuffle_fused", "ccdc_pipeline_fused", "ccdc_pipeline_fused_noalloc", "ccdc_node_encode",
+    "ccdc_node_decode_reduce",
 ]
 
 
@@ -77,7 +78,7 @@ def load_library():
     lib.ccdc_strerror.restype = C.c_char_p
     lib.ccdc_strerror.argtypes = [C.c_int]
     for name, nptr in (("ccdc_combine", 2), ("ccdc_encode", 2), ("ccdc_decode", 3), ("ccdc_reduce", 3),
-                       ("ccdc_shuffle_fused", 3), ("ccdc_pipeline_fused", 3)):
+                       ("ccdc_shuffle_fused", 3), ("ccdc_pipeline_fused", 3), ("ccdc_pipeline_fused_noalloc", 3)):
         fn = getattr(lib, name)
         fn.restype = C.c_int
         fn.argtypes = [vp] + [vp] * nptr + [vp]
@@ -271,6 +272,11 @@ class Plan:
         _check(self._lib.ccdc_pipeline_fused(self._h, self._need(V, "V", "V"), self._need(X, "X", "X"),
                                              self._need(Phi, "Phi", "Phi"), _stream_ptr(stream)),
                "ccdc_pipeline_fused")
+
+    def pipeline_fused_noalloc(self, V, X, Phi, stream=None):
+        _check(self._lib.ccdc_pipeline_fused_noalloc(self._h, self._need(V, "V", "V"), self._need(X, "X", "X"),
+                                                     self._need(Phi, "Phi", "Phi"), _stream_ptr(stream)),
+               "ccdc_pipeline_fused_noalloc")
 
     # ---- the node-local form: node = -1 runs every node
     def node_encode(self, node, V, X, stream=None):

@@ -460,6 +460,7 @@ int ccdc_plan_upload(ccdc_plan_t *plan)
         return rc;
     }
     ccdc::pipeline_prepare(plan);                 // launch geometry of the one-pass kernel on this device
+    (void)ccdc::scratch_address(nullptr);         // set-up for ccdc_pipeline_fused_noalloc, which reports a failure itself
     plan->uploaded = true;
     return CCDC_OK;
 }

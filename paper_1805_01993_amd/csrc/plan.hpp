@@ -116,6 +116,10 @@ void pipeline_prepare(ccdc_plan_t *p);
 int pipeline_entry(const ccdc_plan_t *plan, const void *V, void *X, void *Phi, void *stream, void *own_part,
                    size_t own_part_bytes);
 
+// Device address of the fixed scratch array of ccdc_pipeline_fused_noalloc on the
+// current device (noalloc.hip); out may be null to only look it up ahead of time.
+int scratch_address(void **out);
+
 // Rank of sender a's label among the members other than b.
 inline int label_rank(int a, int b) { return a - (a > b ? 1 : 0); }
 
