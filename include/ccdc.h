@@ -105,7 +105,12 @@ enum ccdc_query {
     CCDC_Q_PACKET_BATCH,     /* int32_t[NROWS]     batch packet i pre-combines  (compression)   */
     CCDC_Q_PACKET_SEND,      /* int32_t[NROWS]     node that sends packet i     (compression)   */
     CCDC_Q_ROWS_PER_NODE,    /* packets every node sends: NROWS / K                   (coded plans)   */
-    CCDC_Q_NODE_ROWS         /* int32_t[K][ROWS_PER_NODE] packets u*(r+1)+a node k sends, ascending   */
+    CCDC_Q_NODE_ROWS,        /* int32_t[K][ROWS_PER_NODE] packets u*(r+1)+a node k sends, ascending   */
+    /* File placement of Sec. IV-A (coded plans; CCDC_ESTATE for ccdc_plan_compression, whose
+     * placement is BATCH_FIRST + NODE_BATCH).  A file is numbered job*N + n. */
+    CCDC_Q_FILE_NODES,       /* int32_t[J*N][r]    the r nodes that store the file, ascending         */
+    CCDC_Q_FILES_PER_NODE,   /* |M_k|: files every node stores, r*J*N/K (= mu*J*N, Sec. IV-A)         */
+    CCDC_Q_NODE_FILES        /* int32_t[K][FILES_PER_NODE] the set M_k: files node k stores, ascending */
 };
 
 /*
@@ -178,7 +183,10 @@ const char *ccdc_strerror(int status);
  * written in full (no accumulation into what they held).  CCDC_EINVAL for a
  * null pointer or one not aligned to the element size; pointers aligned to 16
  * bytes (with T a multiple of 4, or of 8 for 2-byte elements) take the wide
- * kernels, others the one-element kernels with the same results.
+ * kernels, others the one-element kernels with the same results.  A call that
+ * falls back to narrower packs has up to 8 times as many work items as
+ * ccdc_plan_bind checked for: it answers CCDC_ESIZE, before anything is
+ * launched, when one of its launches would pass 2^31-1 of them.
  */
 
 /* Pre-combining (Sec. IV-B): Vbar[u][b][e] = sum over the m files n of the

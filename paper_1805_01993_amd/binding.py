@@ -25,7 +25,7 @@ ELEM_BYTES = {F32_SUM: 4, U32_XOR: 4, F32_SUM_XOR: 4, BF16_SUM_XOR: 2, F16_SUM_X
  Q_D_ELEMS, Q_PHI_ELEMS, Q_WORKSPACE_BYTES) = range(22)
 (Q_PACKET_LEN, Q_BATCH_JOB, Q_BATCH_FILE0, Q_BATCH_LABEL, Q_ROUND_MEMBER, Q_ROUND_BATCH) = range(64, 70)
 (Q_NROWS, Q_SCHEME, Q_BATCH_FIRST, Q_NODE_BATCH, Q_PACKET_RECV, Q_PACKET_BATCH, Q_PACKET_SEND,
- Q_ROWS_PER_NODE, Q_NODE_ROWS) = range(128, 137)
+ Q_ROWS_PER_NODE, Q_NODE_ROWS, Q_FILE_NODES, Q_FILES_PER_NODE, Q_NODE_FILES) = range(128, 140)
 
 EXPORTS = [
     "ccdc_plan", "ccdc_plan_jobs", "ccdc_plan_jobs_repeated", "ccdc_plan_compression", "ccdc_plan_destroy", "ccdc_plan_bind", "ccdc_plan_upload",
@@ -213,6 +213,14 @@ class Plan:
     def node_rows(self):
         """[K][rows per node]: the packets u*(r+1)+a each node sends (coded plans)."""
         return self.query_table(Q_NODE_ROWS, (self.K, self.query(Q_ROWS_PER_NODE)), np.int32)
+
+    def file_nodes(self):
+        """[J*N][r]: the r nodes that store file job*N + n (placement of Sec. IV-A)."""
+        return self.query_table(Q_FILE_NODES, (self.J * self.N, self.r), np.int32)
+
+    def node_files(self):
+        """[K][files per node]: the set M_k of files each node stores, ascending."""
+        return self.query_table(Q_NODE_FILES, (self.K, self.query(Q_FILES_PER_NODE)), np.int32)
 
     def packet_len(self):
         return self.query_table(Q_PACKET_LEN, (1 if self.compression else self.r + 1,), np.int64)

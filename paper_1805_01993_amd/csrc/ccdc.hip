@@ -298,6 +298,7 @@ int run_combine(const ccdc_plan_t *p, const void *V, void *Vbar, hipStream_t st)
     const uint32_t Wv = (uint32_t)(p->W / VEC);
     const uint64_t items = (uint64_t)p->nrows * Wv;
     if (items == 0) return CCDC_OK;
+    if (!fits_launch(items)) return CCDC_ESIZE;
     // short packets, long batches: a wavefront per packet with a cross-lane reduction
 #ifndef CCDC_COMBINE_WAVE_MIN_FILES
 #define CCDC_COMBINE_WAVE_MIN_FILES 8
@@ -323,6 +324,7 @@ int run_encode(const ccdc_plan_t *p, const void *Vbar, void *X, hipStream_t st)
     using E = typename A::elem;
     const uint32_t Wv = (uint32_t)(p->W / VEC), Lv = (uint32_t)(p->ell / VEC);
     const uint64_t items = (uint64_t)p->nround * (p->r + 1) * Lv;
+    if (!fits_launch(items)) return CCDC_ESIZE;
     k_encode<A, VEC><<<cdiv(items, kBlock), kBlock, 0, st>>>((const E *)Vbar, (E *)X, p->r + 1, Lv, Wv,
                                                               (uint32_t)items);
     return launched();
@@ -334,6 +336,7 @@ int run_decode(const ccdc_plan_t *p, const void *X, const void *Vbar, void *D, h
     using E = typename A::elem;
     const uint32_t Wv = (uint32_t)(p->W / VEC), Lv = (uint32_t)(p->ell / VEC);
     const uint64_t items = (uint64_t)p->nround * (p->r + 1) * Wv;
+    if (!fits_launch(items)) return CCDC_ESIZE;
     k_decode<A, VEC><<<cdiv(items, kBlock), kBlock, 0, st>>>((const E *)X, (const E *)Vbar, (E *)D, p->r + 1, Lv,
                                                               Wv, (uint32_t)items);
     return launched();
@@ -352,6 +355,7 @@ void launch_shuffle(const ccdc_plan_t *p, const void *V, void *X, void *D, hipSt
 template <class A, int VEC>
 int run_shuffle(const ccdc_plan_t *p, const void *V, void *X, void *D, hipStream_t st)
 {
+    if (!fits_launch((uint64_t)p->nround * (p->r + 1) * (uint64_t)(p->ell / VEC))) return CCDC_ESIZE;
     switch (p->r + 1) {
     case 2: launch_shuffle<A, VEC, 2>(p, V, X, D, st); break;
     case 3: launch_shuffle<A, VEC, 3>(p, V, X, D, st); break;
@@ -374,6 +378,7 @@ int run_reduce(const ccdc_plan_t *p, const void *V, const void *D, void *Phi, hi
     const int split = p->red_split;
     const uint64_t blocks = (uint64_t)p->nout * split * tiles;
     const int64_t chunk_stride = (int64_t)p->J * p->Q * p->T;
+    if (!fits_launch(blocks) || !fits_launch((uint64_t)chunk_stride / VEC)) return CCDC_ESIZE;
     using Acc = typename A::acc;
     WorkspaceOrder order(p, st, split > 1);
     k_reduce_rows<A, VEC><<<(uint32_t)blocks, kBlock, 0, st>>>((const E *)V, (const E *)D, (E *)Phi,
@@ -498,6 +503,11 @@ int ccdc_plan_query(const ccdc_plan_t *p, int what, void *out, size_t out_bytes)
     case CCDC_Q_PACKET_SEND: return table(p->pkt_send.data(), p->pkt_send.size() * 4);
     case CCDC_Q_ROWS_PER_NODE: return scalar(p->rows_per_node);
     case CCDC_Q_NODE_ROWS: return table(p->node_rows.data(), p->node_rows.size() * 4);
+    case CCDC_Q_FILE_NODES:
+        return p->compression ? (int)CCDC_ESTATE : table(p->file_nodes.data(), p->file_nodes.size() * 4);
+    case CCDC_Q_FILES_PER_NODE: return p->compression ? (int)CCDC_ESTATE : scalar(p->files_per_node);
+    case CCDC_Q_NODE_FILES:
+        return p->compression ? (int)CCDC_ESTATE : table(p->node_files.data(), p->node_files.size() * 4);
     case CCDC_Q_BATCH_JOB: return table(p->batch_job.data(), p->batch_job.size() * 4);
     case CCDC_Q_BATCH_FILE0: return table(p->batch_file0.data(), p->batch_file0.size() * 4);
     case CCDC_Q_BATCH_LABEL: return table(p->batch_label.data(), p->batch_label.size() * 4);

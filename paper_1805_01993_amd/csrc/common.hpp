@@ -207,6 +207,11 @@ __device__ __forceinline__ void store_stream(void *p, const P &v)
 }
 
 constexpr int kBlock = 256;
+// Work items (and workgroups) of one launch are numbered in 32 bits.  ccdc_plan_bind checks the
+// counts for the widest packs a shape allows; a call that has to fall back to narrower packs
+// (pointers not aligned for the wide ones) has more items and checks again for itself.
+constexpr uint64_t kMaxLaunchItems = 2147483647ull;
+inline bool fits_launch(uint64_t items) { return items <= kMaxLaunchItems; }
 
 // Which segment of packet b carries sender a's label: the rank of a among the members other than b.
 __device__ __forceinline__ int segment_rank(int a, int b) { return a - (a > b ? 1 : 0); }

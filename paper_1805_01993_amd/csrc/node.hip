@@ -132,6 +132,7 @@ int run_node_encode(const ccdc_plan_t *p, int node, const void *V, void *X, hipS
     const int64_t rows = node < 0 ? p->nrows : p->rows_per_node;
     const uint64_t items = (uint64_t)rows * Lv;
     if (items == 0) return CCDC_OK;
+    if (!fits_launch(items)) return CCDC_ESIZE;
     const int32_t *list = node < 0 ? nullptr : p->d_node_rows + (size_t)node * p->rows_per_node;
     k_node_encode<A, VEC><<<cdiv(items, kBlock), kBlock, 0, st>>>((const E *)V, (E *)X, p->d_src_off, list, p->r + 1,
                                                                    Lv, Wv, p->m, (int64_t)p->Q * p->T,
@@ -151,6 +152,7 @@ int run_node_decode_reduce(const ccdc_plan_t *p, int node, const void *V, const 
     const uint32_t o_first = node < 0 ? 0u : (uint32_t)node, o_step = node < 0 ? 1u : (uint32_t)p->K;
     const int64_t chunk_stride = (int64_t)p->J * p->Q * p->T;
     const uint64_t blocks = (uint64_t)count * split * tiles;
+    if (!fits_launch(blocks) || !fits_launch((uint64_t)count * Wv)) return CCDC_ESIZE;
     WorkspaceOrder order(p, st, split > 1);
     k_node_decode_reduce<A, VEC><<<(uint32_t)blocks, kBlock, 0, st>>>(
         (const E *)V, (const E *)X, (E *)Phi, (Acc *)p->d_workspace, p->d_red_ptr, p->d_red_row, p->d_red_out,

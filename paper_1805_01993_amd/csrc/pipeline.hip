@@ -336,6 +336,7 @@ int run_pipeline(const ccdc_plan_t *p, const void *V, void *X, void *Phi, void *
     if (!kernel) return CCDC_ESIZE;
     const uint32_t Wv = (uint32_t)(p->W / VEC), Lv = (uint32_t)(p->ell / VEC);
     const uint32_t tiles = pipeline_tiles<VEC>(p);
+    if (!fits_launch((uint64_t)tiles * (uint64_t)chunks) || !fits_launch((uint64_t)p->K * (uint64_t)p->W)) return CCDC_ESIZE;
     kernel<<<tiles * (uint32_t)chunks, ccdc::kPipeLanes, pipeline_lds<VEC>(p), st>>>(
         (const E *)V, (E *)X, (E *)Phi, (Acc *)part, p->d_src_off, p->d_member, p->d_loc_row, p->K, Lv, Wv, p->m,
         (int64_t)p->Q * p->T, (uint32_t)p->nround, tiles, (uint32_t)chunks, (uint32_t)(p->K * p->pipe_local_rows),

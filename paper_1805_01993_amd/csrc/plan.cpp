@@ -203,6 +203,33 @@ int build_plan(int K, int r, int Q, int N, bool paper_jobs, int gamma, ccdc_plan
                 delete p;
                 return CCDC_EINVAL;
             }
+        // placement seen from the files and from the nodes (Sec. IV-A): file -> the label of its
+        // batch; node -> every file of every batch whose label holds it
+        const int64_t nfiles = (int64_t)p->J * N;
+        if (nfiles * r > kMaxTable) {
+            delete p;
+            return CCDC_ESIZE;
+        }
+        p->file_nodes.assign((size_t)nfiles * r, -1);
+        std::vector<std::vector<int32_t>> held((size_t)K);
+        for (int64_t bt = 0; bt < p->nbatch; bt++)
+            for (int f = 0; f < p->m; f++) {
+                const int64_t file = (int64_t)p->batch_job[bt] * N + p->batch_file0[bt] + f;
+                for (int s = 0; s < r; s++) {
+                    p->file_nodes[(size_t)file * r + s] = p->batch_label[bt * r + s];
+                    held[p->batch_label[bt * r + s]].push_back((int32_t)file);
+                }
+            }
+        p->files_per_node = nfiles * r / K;
+        p->node_files.clear();
+        for (int k = 0; k < K; k++) {
+            if ((int64_t)held[k].size() != p->files_per_node) {     // symmetric placement: |M_k| = mu*J*N
+                delete p;
+                return CCDC_EINVAL;
+            }
+            std::sort(held[k].begin(), held[k].end());
+            p->node_files.insert(p->node_files.end(), held[k].begin(), held[k].end());
+        }
     } catch (const std::bad_alloc &) {
         delete p;
         return CCDC_ENOMEM;

@@ -35,6 +35,9 @@ struct ccdc_plan_s {
     std::vector<int32_t> round_batch;   // [nround][r+1]
     std::vector<int32_t> node_rows;     // [K][rows_per_node] packets (u*(r+1)+a) that node k sends, ascending
     int64_t rows_per_node = 0;          // nrows / K: every node is in the same number of rounds
+    std::vector<int32_t> file_nodes;    // [J*N][r] nodes storing file job*N+n, ascending (Sec. IV-A)
+    std::vector<int32_t> node_files;    // [K][files_per_node] the sets M_k, ascending
+    int64_t files_per_node = 0;         // r*J*N/K
 
     // fixed by ccdc_plan_bind
     bool bound = false;

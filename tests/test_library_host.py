@@ -121,6 +121,44 @@ def test_node_rows_list_what_each_node_sends(lib, jobs):
     cp.close()
 
 
+@pytest.mark.parametrize("jobs", [False, True])
+def test_file_placement_queries(lib, jobs):
+    """FILE_NODES and NODE_FILES answer Sec. IV-A's placement directly: file -> the r nodes of
+    its batch label, node k -> the set M_k.  Checked against the oracle's batch tables (built
+    by different code) and against the properties the paper states: every file on exactly r
+    nodes, |M_k| = mu*J*N for every k."""
+    from math import comb
+    for (K, r, c, m) in SWEEP[::2]:
+        nb = (r + 1) if jobs else comb(K, r)
+        while m * nb < K:
+            m += 1
+        N = m * nb
+        p = B.Plan(K, r, c * K, N, jobs=jobs)
+        o = O.build_plan(K, r, c * K, N, "paper" if jobs else "single")
+        want = np.full((o.J * N, r), -1, dtype=np.int32)
+        for bt in range(o.n_batch):
+            first = o.batch_job[bt] * N + o.batch_file0[bt]
+            want[first:first + o.m] = o.batch_label[bt]
+        fn = p.file_nodes()
+        assert np.array_equal(fn, want), (K, r, c, m)
+        assert (np.diff(fn, axis=1) > 0).all() if r > 1 else True           # r distinct nodes, ascending
+        nf = p.node_files()
+        assert nf.shape == (K, r * o.J * N // K)                            # |M_k| = mu*J*N
+        for k in range(K):
+            assert nf[k].tolist() == np.flatnonzero((want == k).any(axis=1)).tolist()
+        p.close()
+    # the paper's K = 3 example: with the 1-based numbers of Sec. II every node stores 4 of the 6 files
+    p = B.ccdc_plan(3, 2, 3, 6)
+    assert p.node_files().shape == (3, 4)
+    assert sorted(np.bincount(p.file_nodes().reshape(-1), minlength=3).tolist()) == [4, 4, 4]
+    p.close()
+    cp = B.ccdc_plan_compression(4, 2, 4, 8)
+    out = np.zeros(64, dtype=np.int32)
+    for what in (B.Q_FILE_NODES, B.Q_FILES_PER_NODE, B.Q_NODE_FILES):
+        assert lib.ccdc_plan_query(cp._h, what, out.ctypes.data_as(C.c_void_p), out.nbytes) == B.ESTATE
+    cp.close()
+
+
 def test_repeated_jobs_plan_equals_the_oracles(lib):
     for (K, r, gamma) in [(4, 2, 2), (5, 2, 3), (4, 3, 4), (6, 1, 2)]:
         N = (r + 1) * max(1, -(-K // (r + 1)))
