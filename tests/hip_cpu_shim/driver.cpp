@@ -42,8 +42,36 @@ static float widen16(uint16_t b, bool bf)
     return (float)h;
 }
 
+// A shape whose work items fit 32 bits with four-element packs but not with one-element packs:
+// ccdc_plan_bind accepts it; a call with pointers that are only 4-byte aligned falls back to
+// one-element packs and must be refused with CCDC_ESIZE before anything is launched (the
+// pointers given here point nowhere: a launch would be caught by the sanitizer).
+static int limits()
+{
+    const int K = 4, r = 2, Q = 4, N = 6;
+    const int64_t T = 200000000;
+    ccdc_plan_t *p = nullptr;
+    CHECK(ccdc_plan(K, r, Q, N, &p));
+    CHECK(ccdc_plan_bind(p, T, CCDC_U32_XOR));
+    CHECK(ccdc_plan_upload(p));
+    const long before = shim::launches.load();
+    void *a = reinterpret_cast<void *>(0x1004), *b = reinterpret_cast<void *>(0x2004), *c = reinterpret_cast<void *>(0x3004);
+    int bad = 0;
+    // combine and decode have one work item per pack of a W-long packet: 12 * 2e8 > 2^31 - 1
+    // (the encoders have one per pack of a segment, r times fewer: those still fit)
+    bad += ccdc_combine(p, a, b, nullptr) != CCDC_ESIZE;
+    bad += ccdc_decode(p, a, b, c, nullptr) != CCDC_ESIZE;
+    bad += shim::launches.load() != before;
+    // a value length past what any pack width indexes is refused when the plan is bound
+    bad += ccdc_plan_bind(p, (int64_t)1 << 38, CCDC_U32_XOR) != CCDC_ESIZE;
+    ccdc_plan_destroy(p);
+    std::printf(bad ? "limits FAILED (%d)\n" : "limits ok\n", bad);
+    return bad ? 1 : 0;
+}
+
 int main(int argc, char **argv)
 {
+    if (argc == 2 && std::strcmp(argv[1], "limits") == 0) return limits();
     if (argc < 8) return 64;
     const int K = atoi(argv[1]), r = atoi(argv[2]), Q = atoi(argv[3]), N = atoi(argv[4]);
     const int64_t T = atoll(argv[5]);

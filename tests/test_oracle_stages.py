@@ -308,3 +308,51 @@ def test_repeated_scheme_recovers_every_output(mode):
     V = make_inputs(p, 5, mode, seed=77)
     art = O.run_all(p, 5, V)
     assert np.array_equal(art["Phi"], O.direct(p, 5, V)) and np.array_equal(art["D"], art["Vbar"])
+
+
+# ---------------------------------------------------------------- sampling a schedule
+
+@pytest.mark.parametrize("K,r,c,m,T,schedule", [(5, 2, 1, 1, 12, "single"), (6, 3, 2, 2, 10, "single"),
+                                                 (4, 2, 1, 2, 7, "paper"), (5, 2, 2, 1, 9, "paper")])
+def test_a_plan_of_selected_rounds_gives_the_parents_rows(K, r, c, m, T, schedule):
+    """orc_plan_select_rounds keeps the batches and takes the listed rounds, in the order
+    listed: its tables are the parent's rows, and every artefact of the stages run on it
+    (Vbar, X, D) equals the parent's artefact at those rounds, in both algebras.  Repeats
+    and arbitrary order are allowed; a bad index is refused."""
+    from math import comb
+    nb = (r + 1) if schedule == "paper" else comb(K, r)
+    while m * nb < K:
+        m += 1
+    plan = O.build_plan(K, r, c * K, m * nb, schedule)
+    rng = np.random.default_rng(K * 100 + r)
+    rounds = rng.permutation(plan.n_round)[: max(1, plan.n_round // 2)].tolist()
+    rounds += [rounds[0], plan.n_round - 1, 0]                       # repeats, last and first
+    sub = O.select_rounds(plan, rounds)
+    assert (sub.K, sub.r, sub.Q, sub.N, sub.J, sub.c, sub.m, sub.n_batch) == \
+           (plan.K, plan.r, plan.Q, plan.N, plan.J, plan.c, plan.m, plan.n_batch)
+    assert sub.n_round == len(rounds)
+    for name in ("batch_job", "batch_file0", "batch_label"):
+        assert np.array_equal(getattr(sub, name), getattr(plan, name)), name
+    assert np.array_equal(sub.round_member, plan.round_member[rounds])
+    assert np.array_equal(sub.round_batch, plan.round_batch[rounds])
+    for dtype in (np.uint32, np.float32):
+        if dtype == np.uint32:
+            V = rng.integers(0, 2 ** 32, size=plan.shapes(T)["V"], dtype=np.uint64).astype(np.uint32)
+        else:
+            V = rng.integers(-50, 50, size=plan.shapes(T)["V"]).astype(np.float32)
+        full = O.run_all(plan, T, V)
+        vb = O.combine(sub, T, V)
+        xs = O.encode(sub, T, vb)
+        ds = O.decode(sub, T, xs, vb)
+        assert np.array_equal(vb, full["Vbar"][rounds])
+        assert np.array_equal(xs, full["X"][rounds])
+        assert np.array_equal(ds, full["D"][rounds])
+    if plan.J == 1:
+        h = O.run_all_h32(plan, T, V)
+        hs = O.run_all_h32(sub, T, V)
+        for name in ("Vbar", "X", "D"):
+            assert np.array_equal(hs[name].view(np.uint32), h[name].view(np.uint32)[rounds]), name
+    assert O.select_rounds(plan, []).n_round == 0
+    for bad in ([-1], [plan.n_round], [0, plan.n_round + 5]):
+        with pytest.raises(ValueError):
+            O.select_rounds(plan, bad)
