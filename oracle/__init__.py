@@ -11,10 +11,13 @@ from .ccdc_oracle import (  # noqa: F401
     build_plan,
     closed_form_elems,
     combine,
+    combine_h32,
     decode,
+    decode_h32,
     direct,
     direct_h16,
     encode,
+    encode_h32,
     h16_narrow,
     h16_widen,
     label_rank,
@@ -27,4 +30,5 @@ from .ccdc_oracle import (  # noqa: F401
     segment_count,
     segment_len,
     select_rounds,
+    shuffle_h16,
 )

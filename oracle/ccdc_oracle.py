@@ -318,6 +318,31 @@ class CompressionPlan:
         return out
 
 
+def combine_h32(plan, T, V):
+    sh = plan.shapes(T)
+    _check(V, np.float32, sh["V"], "V")
+    out = np.empty(sh["Vbar"], dtype=np.float32)
+    _load().orc_combine_h32(plan._ptr, T, _ptr(V), _ptr(out))
+    return out
+
+
+def encode_h32(plan, T, Vbar):
+    sh = plan.shapes(T)
+    _check(Vbar, np.float32, sh["Vbar"], "Vbar")
+    out = np.empty(sh["X"], dtype=np.uint32)
+    _load().orc_encode_h32(plan._ptr, T, _ptr(Vbar), _ptr(out))
+    return out
+
+
+def decode_h32(plan, T, X, Vbar):
+    sh = plan.shapes(T)
+    _check(X, np.uint32, sh["X"], "X")
+    _check(Vbar, np.float32, sh["Vbar"], "Vbar")
+    out = np.zeros(sh["D"], dtype=np.float32)
+    _load().orc_decode_h32(plan._ptr, T, _ptr(X), _ptr(Vbar), _ptr(out))
+    return out
+
+
 def run_all_h32(plan, T, V):
     """The "h32" algebra: fp32 sums when pre-combining, XOR of bit patterns to code
     and decode, fp64 final reduction.  Vbar/D float32, X uint32, Phi float64."""
@@ -381,6 +406,23 @@ def run_all_h16(plan, T, V, fmt):
     lib.orc_decode_h16(plan._ptr, T64, _ptr(X), _ptr(Vbar), _ptr(D))
     lib.orc_reduce_h16(plan._ptr, T64, f, _ptr(V), _ptr(D), _ptr(Phi))
     return {"Vbar": Vbar, "X": X, "D": D, "Phi": Phi}
+
+
+def shuffle_h16(plan, T, V, fmt):
+    """The three shuffle stages of the "h16" algebra without the final reduction:
+    Vbar, X, D as uint16 patterns."""
+    lib = _load()
+    f = H16_FORMATS[fmt]
+    sh = plan.shapes(T)
+    _check(V, np.uint16, sh["V"], "V")
+    Vbar = np.empty(sh["Vbar"], dtype=np.uint16)
+    X = np.empty(sh["X"], dtype=np.uint16)
+    D = np.zeros(sh["D"], dtype=np.uint16)
+    T64 = C.c_int64(T)
+    lib.orc_combine_h16(plan._ptr, T64, f, _ptr(V), _ptr(Vbar))
+    lib.orc_encode_h16(plan._ptr, T64, _ptr(Vbar), _ptr(X))
+    lib.orc_decode_h16(plan._ptr, T64, _ptr(X), _ptr(Vbar), _ptr(D))
+    return {"Vbar": Vbar, "X": X, "D": D}
 
 
 def direct_h16(plan, T, V, fmt):
