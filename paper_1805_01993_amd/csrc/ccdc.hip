@@ -29,7 +29,12 @@ __global__ __launch_bounds__(kBlock) void k_combine(const typename A::elem *__re
     const uint32_t row = idx / Wv, e = idx - row * Wv;
     const typename A::elem *src = V + src_off[row] + (int64_t)e * VEC;
     const int files = row_files ? row_files[row] : m;
-    typename O::Q acc = O::widen(load_stream<P>(src));
+    const P first = load_stream<P>(src);
+    if (files == 1) {                                 // not a sum: the packet is the file's values as they are
+        reinterpret_cast<P *>(Vbar)[idx] = first;
+        return;
+    }
+    typename O::Q acc = O::widen(first);
     for (int f = 1; f < files; f++) acc = O::accum(acc, load_stream<P>(src + f * file_stride));
     reinterpret_cast<P *>(Vbar)[idx] = O::narrow(acc);
 }
@@ -162,7 +167,9 @@ __global__ __launch_bounds__(kBlock) void k_shuffle_fused(const typename A::elem
         const uint32_t pos = segment_rank(a, b) * Lv + x;
         if (pos >= Wv) return O::zero();
         const typename A::elem *s = V + src[b] + (int64_t)pos * VEC;
-        typename O::Q acc = O::widen(load_stream<P>(s));
+        const P first = load_stream<P>(s);
+        if (m == 1) return first;                     // a one-file batch is sent as it is
+        typename O::Q acc = O::widen(first);
         for (int f = 1; f < m; f++) acc = O::accum(acc, load_stream<P>(s + f * file_stride));
         return O::narrow(acc);
     };

@@ -58,7 +58,10 @@ struct HybF32 {                       // numbers are summed, packets are XOR-cod
 };
 // The same hybrid for 16-bit floating-point payloads: elements are bit patterns
 // of bfloat16 (BF) or IEEE binary16 numbers, sums are carried in fp32 and
-// rounded once, to nearest even, when stored.
+// rounded once, to nearest even, when stored.  A batch of one file is not a sum:
+// its packet is the file's values as they are, pattern for pattern (every kernel
+// copies in that case), so signalling or signed NaN patterns in the input pass
+// through the coding untouched.
 template <bool BF>
 struct Hyb16 {
     using elem = uint16_t;
@@ -76,15 +79,19 @@ struct Hyb16 {
             return (float)h;
         }
     }
+    // A sum that is not a number is stored as the format's quiet NaN with a clear sign and
+    // payload (0x7FC0 / 0x7E00), whatever NaN the additions produced.
     static __device__ __forceinline__ elem narrow(acc a)
     {
         if constexpr (BF) {
+            if (a != a) return (elem)0x7FC0u;
+            // keep the upper 16 bits; round up when the dropped half is above the midpoint, or
+            // on it with an odd kept part (the increment may carry into the exponent, up to infinity)
             const uint32_t b = __float_as_uint(a);
-            if (a != a) return (elem)((b >> 16) | 0x7FC0u);
-            // drop 16 fraction bits: add half of the dropped range, one less when the
-            // kept part is even; a carry runs into the exponent (up to infinity)
-            return (elem)((b + 0x7FFFu + ((b >> 16) & 1u)) >> 16);
+            const uint32_t kept = b >> 16, dropped = b & 0xFFFFu;
+            return (elem)(kept + ((dropped > 0x8000u || (dropped == 0x8000u && (kept & 1u))) ? 1u : 0u));
         } else {
+            if (a != a) return (elem)0x7E00u;
             const _Float16 h = (_Float16)a;              // the hardware conversion rounds to nearest even
             elem out;
             __builtin_memcpy(&out, &h, 2);

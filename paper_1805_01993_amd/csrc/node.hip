@@ -17,7 +17,9 @@ __device__ __forceinline__ typename Ops<A, VEC>::P combined_pack(const typename 
     using O = Ops<A, VEC>;
     using P = typename O::P;
     const typename A::elem *s = V + src + (int64_t)pos * VEC;
-    typename O::Q acc = O::widen(load_stream<P>(s));
+    const P first = load_stream<P>(s);
+    if (m == 1) return first;                         // a one-file batch is sent as it is
+    typename O::Q acc = O::widen(first);
     for (int f = 1; f < m; f++) acc = O::accum(acc, load_stream<P>(s + f * file_stride));
     return O::narrow(acc);
 }

@@ -145,6 +145,65 @@ def test_random_shapes(torch, L, seed):
     run_case(torch, L, K, r, c * K, m * nb, T, FORMATS[seed % 2], jobs=jobs, seed=seed)
 
 
+CANON_NAN = {"bf16": 0x7FC0, "f16": 0x7E00}
+INF = {"bf16": 0x7F80, "f16": 0x7C00}
+LARGEST = {"bf16": 3.3895314e38, "f16": 65504.0}
+
+
+@pytest.mark.parametrize("K,r,Q,N,T", [(5, 2, 5, 10, 1024),      # one-file batches: packets are the files' patterns
+                                       (5, 2, 5, 20, 1024),      # m = 2: every packet is a rounded sum
+                                       (4, 3, 8, 12, 100),       # m = 3, c = 2, short last segment, 8-byte packs
+                                       (6, 2, 6, 30, 7)])        # m = 2, one-element packs
+@pytest.mark.parametrize("fmt", FORMATS)
+def test_special_patterns_in_the_payload(torch, L, K, r, Q, N, T, fmt):
+    """Infinities, quiet and signalling NaNs with payloads and signs, subnormals, the largest
+    finite values, sums that leave the format: packets (Vbar, X, D) of every path must equal
+    the oracle's bit for bit (a sum that is not a number is stored as the one canonical NaN
+    pattern on both sides, a one-file batch passes through untouched); an output is NaN
+    exactly where the exact sum is, the same infinity where that is infinite, and within the
+    rounding bound elsewhere."""
+    from workloads import special_payload
+    op = O.build_plan(K, r, Q, N)
+    Vh = special_payload(op.shapes(T)["V"], fmt, seed=K * 100 + r * 10 + T % 7, density=0.03)
+    ref = O.run_all_h16(op, T, Vh, fmt)
+    plan = L.Plan(K, r, Q, N).bind(T, fmt).upload()
+    sh = plan.shapes()
+    V = to_dev(torch, Vh)
+    Vbar, X, D, Phi = (dev_poison(torch, sh[k]) for k in ("Vbar", "X", "D", "Phi"))
+    plan.combine(V, Vbar)
+    plan.encode(Vbar, X)
+    plan.decode(X, Vbar, D)
+    plan.reduce(V, D, Phi)
+    X2, D2, X3, Phi3, X4, Phi4 = (dev_poison(torch, sh[k]) for k in ("X", "D", "X", "Phi", "X", "Phi"))
+    plan.shuffle_fused(V, X2, D2)
+    plan.pipeline_fused(V, X3, Phi3)
+    plan.node_encode(-1, V, X4)
+    plan.node_decode_reduce(-1, V, X4, Phi4)
+    torch.cuda.synchronize()
+    for name, t in (("Vbar", Vbar), ("X", X), ("D", D), ("fused X", X2), ("fused D", D2), ("pipeline X", X3),
+                    ("node-local X", X4)):
+        assert_bits(to_host(t), ref[name.split()[-1]], name)
+    want = ref["Phi"]
+    # outputs whose finite terms cannot overflow an fp32 partial sum in any order: elsewhere
+    # (bfloat16 only) the kernels' fp32 running sum may pass through infinity where the exact
+    # sum does not, and nothing is claimed
+    vals = half_bits_to_float(Vh, fmt).astype(np.float64)
+    safe = np.where(np.isfinite(vals), np.abs(vals), 0.0).sum(axis=1) <= 1e38
+    nan, inf = np.isnan(want), np.isinf(want) & safe
+    assert nan.any() and (op.m > 1 or inf.any())
+    plain = np.isfinite(want) & safe & (np.abs(want) <= LARGEST[fmt] * (1 - 2.0 ** -8))
+    for name, t in (("Phi", Phi), ("pipeline Phi", Phi3), ("node-local Phi", Phi4)):
+        got = to_host(t)
+        assert (got[nan] == CANON_NAN[fmt]).all(), name
+        assert np.array_equal(got[inf], np.where(want[inf] > 0, INF[fmt], 0x8000 | INF[fmt]).astype(np.uint16)), name
+        val = half_bits_to_float(got[plain], fmt).astype(np.float64)
+        scale = float(np.abs(want[plain]).max())
+        over = np.abs(val - want[plain]) - (HALF_ULP[fmt] * 1.001 * np.abs(want[plain]) + F32_TOL * scale
+                                            + (2.0 ** -25 if fmt == "f16" else 0.0))
+        assert over.max() <= 0, f"{name}: exceeds the rounding bound by {over.max():.3e}"
+    plan.close()
+
+
 @pytest.mark.parametrize("fmt", FORMATS)
 def test_two_byte_aligned_pointers(torch, L, fmt):
     """Buffers that are only 2-byte aligned take the one-element path; odd addresses are refused."""

@@ -184,3 +184,92 @@ def test_h16_ragged_split(fmt):
     art = O.run_all_h16(p, T, V, fmt)
     assert art["X"].shape == (1, 4, 4) and (art["X"][0, 3, 2:] == 0).all()
     assert np.array_equal(art["D"], art["Vbar"])
+
+
+# ------------------------------------------------ special patterns in the payload
+
+CANON_NAN = {"bf16": 0x7FC0, "f16": 0x7E00}
+EXP_MASK = {"bf16": 0x7F80, "f16": 0x7C00}
+FRAC_MASK = {"bf16": 0x007F, "f16": 0x03FF}
+
+
+def is_nan_bits(bits, fmt):
+    return ((bits & EXP_MASK[fmt]) == EXP_MASK[fmt]) & ((bits & FRAC_MASK[fmt]) != 0)
+
+
+@pytest.mark.parametrize("fmt", FORMATS)
+def test_a_sum_that_is_not_a_number_is_stored_as_the_canonical_nan(fmt):
+    """Every NaN the conversion can be handed (any sign, any payload, quiet or signalling)
+    comes out as the one quiet pattern with sign and payload clear; infinities keep their
+    sign; values past the largest finite one round to infinity."""
+    nans = np.array([0x7FC00000, 0xFFC00000, 0x7F800001, 0xFF800001, 0x7FFFFFFF, 0xFFFFFFFF, 0x7FA55555],
+                    dtype=np.uint32).view(np.float32)
+    assert (O.h16_narrow(nans, fmt) == CANON_NAN[fmt]).all()
+    inf = np.array([np.inf, -np.inf], dtype=np.float32)
+    assert O.h16_narrow(inf, fmt).tolist() == [EXP_MASK[fmt], 0x8000 | EXP_MASK[fmt]]
+    big = np.array([3.4e38, -3.4e38] if fmt == "bf16" else [65520.0, -1e6], dtype=np.float32)
+    assert O.h16_narrow(big, fmt).tolist() == [EXP_MASK[fmt], 0x8000 | EXP_MASK[fmt]]
+
+
+@pytest.mark.parametrize("fmt", FORMATS)
+@pytest.mark.parametrize("m", [1, 2, 3])
+def test_special_patterns_through_the_stages(fmt, m):
+    """Payloads holding infinities, NaNs of every kind, subnormals and the largest finite
+    values.  One-file batches (m = 1) are not sums: the packet is the file's patterns
+    untouched, NaN payloads included.  Longer batches: the fp32 sum of the exact values,
+    files ascending, rounded once - checked against numpy / torch doing exactly that in
+    their own arithmetic - with every NaN stored as the canonical pattern, sums of opposite
+    infinities included, and sums past the format's range stored as infinity.  Coding is on
+    patterns, so every receiver recovers every packet bit for bit whatever it holds."""
+    from workloads import special_payload
+    K, r, c, T = 5, 2, 1, 24
+    plan = O.build_plan(K, r, c * K, m * comb(K, r))
+    V = special_payload(plan.shapes(T)["V"], fmt, seed=7 * m, density=0.2)
+    assert is_nan_bits(V, fmt).any() and (V == EXP_MASK[fmt]).any()
+    out = O.run_all_h16(plan, T, V, fmt)
+    Vbar, r1 = out["Vbar"], r + 1
+    vals = lib_widen(V, fmt)
+    saw_nan_sum = False
+    for u in range(plan.n_round):
+        for b in range(r1):
+            target, bt = int(plan.round_member[u, b]), int(plan.round_batch[u, b])
+            f0 = int(plan.batch_file0[bt])
+            if m == 1:
+                assert np.array_equal(Vbar[u, b], V[0, f0, target])              # untouched, pattern for pattern
+                continue
+            acc = vals[0, f0, target].copy()
+            with np.errstate(invalid="ignore", over="ignore"):
+                for n in range(f0 + 1, f0 + m):
+                    acc = (acc + vals[0, n, target]).astype(np.float32)
+            want = lib_narrow(acc, fmt)
+            nan = np.isnan(acc)
+            assert np.array_equal(Vbar[u, b][~nan], want[~nan])
+            assert (Vbar[u, b][nan] == CANON_NAN[fmt]).all()
+            saw_nan_sum |= bool(nan.any())
+    assert m == 1 or saw_nan_sum
+    assert np.array_equal(out["D"], Vbar)                                         # exact recovery of any pattern
+    # the final reduction is exact fp64 arithmetic on the values: NaN where a NaN or opposite
+    # infinities meet, else the plain sum
+    with np.errstate(invalid="ignore"):
+        direct = lib_widen(V, fmt).astype(np.float64).sum(axis=1)
+    got = out["Phi"]
+    if m == 1:
+        assert np.array_equal(np.isnan(got), np.isnan(direct))
+        ok = ~np.isnan(direct)
+        assert np.array_equal(got[ok], direct[ok])
+
+
+@pytest.mark.parametrize("fmt", FORMATS)
+def test_sums_that_leave_the_format(fmt):
+    """Two largest finite values add up, in fp32, to a number the format cannot hold:
+    the pre-combined packet stores infinity (binary16: 65504 + 65504; bfloat16: the fp32
+    sum itself overflows)."""
+    top = {"bf16": 0x7F7F, "f16": 0x7BFF}[fmt]
+    plan = O.build_plan(3, 2, 3, 6)                                               # m = 2
+    T = 4
+    V = np.full(plan.shapes(T)["V"], top, dtype=np.uint16)
+    V[0, 1::2] = top | 0x8000                                                    # second file of each batch: the negative
+    V[0, :, :, 0] = top                                                           # column 0: both positive
+    out = O.run_all_h16(plan, T, V, fmt)
+    assert (out["Vbar"][..., 0] == EXP_MASK[fmt]).all()                           # +inf
+    assert (out["Vbar"][..., 1:] == 0).all()                                      # top + (-top) = +0

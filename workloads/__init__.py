@@ -5,3 +5,4 @@ see bit-identical inputs.  Holds none of the method's arithmetic.
 """
 from .configs import CONFIGS, Workload, get  # noqa: F401
 from .generator import generate_numpy, generate_torch, half_bits_to_float, to_half_bits  # noqa: F401
+from .special16 import SPECIAL, special_payload  # noqa: F401

@@ -56,14 +56,14 @@ def generate_numpy(J, N, Q, T, seed, mode, sigma=1.0):
 
 
 def to_half_bits(values, mode):
-    """uint16 patterns of float32 values rounded to nearest even: "f16" through
-    numpy's float16, "bf16" by rounding away the low 16 bits of the fp32 pattern."""
+    """uint16 patterns of float32 values rounded to nearest even, by the array libraries'
+    own conversions: numpy's float16 for "f16", torch's bfloat16 for "bf16"."""
     values = np.ascontiguousarray(values, dtype=np.float32)
     if mode == "f16":
         with np.errstate(over="ignore"):
             return values.astype(np.float16).view(np.uint16)
-    b = values.view(np.uint32).astype(np.uint64)
-    return ((b + np.uint64(0x7FFF) + ((b >> np.uint64(16)) & np.uint64(1))) >> np.uint64(16)).astype(np.uint16)
+    import torch
+    return torch.from_numpy(values).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
 
 
 def half_bits_to_float(bits, mode):
