@@ -21,8 +21,8 @@
  *   D    [R][r+1][W]      packet decoded by member b in round u
  *   Phi  [J][Q][T]        reduced outputs
  * Subsets (batch labels and rounds) are numbered in lexicographic order.
- * When r does not divide W the split "evenly into mu*K segments" (Sec. IV-B)
- * is read as: ell = W/r if 4r | W, else ceil(W/r) rounded up to a multiple of
+ * Sec. IV-B cuts a packet into r segments of equal length; when r does not
+ * divide W that is read as: ell = W/r if 4r | W, else ceil(W/r) rounded up to a multiple of
  * 4; segment rho = [rho*ell, min(W,(rho+1)*ell)), the tail may be short/empty.
  *
  * Payload modes: CCDC_F32_SUM (fp32, real + to combine/encode/reduce, real -
@@ -176,6 +176,21 @@ int ccdc_plan_query(const ccdc_plan_t *plan, int what, void *out, size_t out_byt
 const char *ccdc_strerror(int status);
 
 /*
+ * A stand-in for the Map phase (Sec. III: node k maps every file it stores into the Q
+ * intermediate values v_{q,n} = g_q(w_n); the paper leaves g_q free).  A file is a data
+ * vector of Q*T elements, files = [J][N][Q][T] like V; every job has a model
+ * theta = [J][Q][T]; the map is the gradient of 1/2 |theta - w_n|^2 chunk by chunk,
+ *     V[j][n][q][t] = theta[j][q][t] - files[j][n][q][t]
+ * (XOR in CCDC_U32_XOR; in the 16-bit modes the fp32 difference rounded once to the
+ * format).  The shuffle path then sums it over the files: Phi = N*theta - sum_n w_n.
+ * Every file is mapped once per call (the r nodes that store it would compute the same
+ * values).  V may be the files buffer itself (the values replace the files in place) or
+ * a separate one; theta must not overlap V.  Device pointers, errors and alignment rules
+ * as for the stage calls below; any coded or uncoded plan.
+ */
+int ccdc_map(const ccdc_plan_t *plan, const void *files, const void *theta, void *V, void *stream);
+
+/*
  * The four stages.  All pointers are device pointers; see the buffer table
  * above for shapes.  Each needs an uploaded plan (CCDC_ESTATE otherwise) and
  * the plan's device to be current.  The caller owns every buffer and keeps it
@@ -244,7 +259,7 @@ int ccdc_pipeline_fused_noalloc(const ccdc_plan_t *plan, const void *V, void *X,
 /*
  * The node-local form of the path: what ONE node of the cluster does in the
  * shuffle, from nothing but the files it stores and the coded packets it
- * receives (Sec. IV-B, "for each k in K": pre-combine, split, code, multicast;
+ * receives (Sec. IV-B, the steps every member of a subset takes: pre-combine, split, code, multicast;
  * then decode with locally computed side information and reduce).  V and X are
  * the same arrays as above, but node k's calls read only the files k stores
  * (its batches, Sec. IV-A) and the packets sent to k, so X plays the network.

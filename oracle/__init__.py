@@ -21,6 +21,7 @@ from .ccdc_oracle import (  # noqa: F401
     h16_narrow,
     h16_widen,
     label_rank,
+    map_files,
     packet_len,
     reduce,
     run_all,

@@ -543,3 +543,41 @@ int64_t orc_cplan_scheduled_elems(const orc_cplan *p, int64_t T)
  * Hybrid scheme for 16-bit floating-point payloads.
  */
 #include "ccdc_oracle_h16.inc"
+
+/* ---------------------------------------------------------------- Map stand-in
+ * Sec. III, Map phase: v_{q,n} = g_q(w_n) for every file.  Here g is the gradient of
+ * 1/2 |theta - w_n|^2, chunk q of it: theta_q - w_{n,q}. */
+void orc_map_f32(int J, int N, int Q, int64_t T, const float *files, const float *theta, float *V)
+{
+    for (int j = 0; j < J; j++)
+        for (int n = 0; n < N; n++)
+            for (int q = 0; q < Q; q++)
+                for (int64_t t = 0; t < T; t++) {
+                    const int64_t at = (((int64_t)j * N + n) * Q + q) * T + t;
+                    volatile float d = theta[((int64_t)j * Q + q) * T + t] - files[at];
+                    V[at] = d;
+                }
+}
+
+void orc_map_u32(int J, int N, int Q, int64_t T, const uint32_t *files, const uint32_t *theta, uint32_t *V)
+{
+    for (int j = 0; j < J; j++)
+        for (int n = 0; n < N; n++)
+            for (int q = 0; q < Q; q++)
+                for (int64_t t = 0; t < T; t++) {
+                    const int64_t at = (((int64_t)j * N + n) * Q + q) * T + t;
+                    V[at] = theta[((int64_t)j * Q + q) * T + t] ^ files[at];
+                }
+}
+
+void orc_map_h16(int J, int N, int Q, int64_t T, int fmt, const uint16_t *files, const uint16_t *theta, uint16_t *V)
+{
+    for (int j = 0; j < J; j++)
+        for (int n = 0; n < N; n++)
+            for (int q = 0; q < Q; q++)
+                for (int64_t t = 0; t < T; t++) {
+                    const int64_t at = (((int64_t)j * N + n) * Q + q) * T + t;
+                    volatile float d = h16_widen(theta[((int64_t)j * Q + q) * T + t], fmt) - h16_widen(files[at], fmt);
+                    V[at] = h16_narrow(d, fmt);
+                }
+}

@@ -84,7 +84,7 @@ void orc_plan_free(orc_plan *p);
 /* Same batches, only the listed rounds (for sampling a large schedule); NULL on bad index. */
 orc_plan *orc_plan_select_rounds(const orc_plan *src, const int64_t *rounds, int64_t n);
 /* J = gamma * (jobs of src): the same placement and rounds repeated gamma times on
- * consecutive blocks of jobs (Sec. IV, "repeats the same operations gamma times"). */
+ * consecutive blocks of jobs (Sec. IV: with gamma times as many jobs the scheme is run gamma times over). */
 orc_plan *orc_plan_repeat(const orc_plan *src, int gamma);
 
 /* Segment length ell for a packet of W elements cut into r segments. */
@@ -165,6 +165,17 @@ void orc_encode_h16 (const orc_plan *p, int64_t T, const uint16_t *Vbar, uint16_
 void orc_decode_h16 (const orc_plan *p, int64_t T, const uint16_t *X, const uint16_t *Vbar, uint16_t *D);
 void orc_reduce_h16 (const orc_plan *p, int64_t T, int fmt, const uint16_t *V, const uint16_t *D, double *Phi);
 void orc_direct_h16 (const orc_plan *p, int64_t T, int fmt, const uint16_t *V, double *Phi);   /* eq. (1) */
+
+/*
+ * Stand-in for the Map phase (Sec. III): a file is a data vector of Q*T elements, a job has
+ * a model theta of Q*T elements, and the intermediate values are the chunks of the gradient
+ * of 1/2 |theta - w_n|^2:  V[j][n][q][t] = theta[j][q][t] - files[j][n][q][t].
+ * f32: one fp32 subtraction (the values ARE fp32: they are the inputs of the stages);
+ * u32: XOR; h16: the fp32 difference of the two exact values, rounded once to the format.
+ */
+void orc_map_f32(int J, int N, int Q, int64_t T, const float *files, const float *theta, float *V);
+void orc_map_u32(int J, int N, int Q, int64_t T, const uint32_t *files, const uint32_t *theta, uint32_t *V);
+void orc_map_h16(int J, int N, int Q, int64_t T, int fmt, const uint16_t *files, const uint16_t *theta, uint16_t *V);
 
 #ifdef __cplusplus
 }

@@ -432,3 +432,23 @@ def direct_h16(plan, T, V, fmt):
     out = np.empty(sh["Phi"], dtype=np.float64)
     _load().orc_direct_h16(plan._ptr, C.c_int64(T), H16_FORMATS[fmt], _ptr(V), _ptr(out))
     return out
+
+
+def map_files(files, theta, fmt=None):
+    """Map stand-in (Sec. III): V[j][n][q][t] = theta[j][q][t] - files[j][n][q][t].
+    float32 arrays: one fp32 subtraction; uint32: XOR; uint16 patterns with fmt "bf16" /
+    "f16": the fp32 difference rounded once to the format."""
+    lib = _load()
+    J, N, Q, T = files.shape
+    _check(files, files.dtype, (J, N, Q, T), "files")
+    _check(theta, files.dtype, (J, Q, T), "theta")
+    out = np.empty_like(files)
+    if files.dtype == np.float32:
+        lib.orc_map_f32(J, N, Q, C.c_int64(T), _ptr(files), _ptr(theta), _ptr(out))
+    elif files.dtype == np.uint32:
+        lib.orc_map_u32(J, N, Q, C.c_int64(T), _ptr(files), _ptr(theta), _ptr(out))
+    elif files.dtype == np.uint16:
+        lib.orc_map_h16(J, N, Q, C.c_int64(T), H16_FORMATS[fmt], _ptr(files), _ptr(theta), _ptr(out))
+    else:
+        raise TypeError(f"unsupported dtype {files.dtype}")
+    return out

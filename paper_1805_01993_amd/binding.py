@@ -29,7 +29,7 @@ ELEM_BYTES = {F32_SUM: 4, U32_XOR: 4, F32_SUM_XOR: 4, BF16_SUM_XOR: 2, F16_SUM_X
 
 EXPORTS = [
     "ccdc_plan", "ccdc_plan_jobs", "ccdc_plan_jobs_repeated", "ccdc_plan_compression", "ccdc_plan_destroy", "ccdc_plan_bind", "ccdc_plan_upload",
-    "ccdc_plan_query", "ccdc_strerror", "ccdc_combine", "ccdc_encode", "ccdc_decode", "ccdc_reduce",
+    "ccdc_plan_query", "ccdc_strerror", "ccdc_map", "ccdc_combine", "ccdc_encode", "ccdc_decode", "ccdc_reduce",
     "ccdc_shuffle_fused", "ccdc_pipeline_fused", "ccdc_pipeline_fused_noalloc", "ccdc_node_encode",
     "ccdc_node_decode_reduce",
 ]
@@ -78,7 +78,8 @@ def load_library():
     lib.ccdc_strerror.restype = C.c_char_p
     lib.ccdc_strerror.argtypes = [C.c_int]
     for name, nptr in (("ccdc_combine", 2), ("ccdc_encode", 2), ("ccdc_decode", 3), ("ccdc_reduce", 3),
-                       ("ccdc_shuffle_fused", 3), ("ccdc_pipeline_fused", 3), ("ccdc_pipeline_fused_noalloc", 3)):
+                       ("ccdc_shuffle_fused", 3), ("ccdc_pipeline_fused", 3), ("ccdc_pipeline_fused_noalloc", 3),
+                       ("ccdc_map", 3)):
         fn = getattr(lib, name)
         fn.restype = C.c_int
         fn.argtypes = [vp] + [vp] * nptr + [vp]
@@ -254,6 +255,11 @@ class Plan:
         if t.numel() != want:
             raise ValueError(f"{name}: need {want} elements, got {t.numel()}")
         return _dev_ptr(t, name, self._elem_bytes)
+
+    # ---- Map stand-in: V = theta - files (V may be the files tensor itself)
+    def map(self, files, theta, V, stream=None):
+        _check(self._lib.ccdc_map(self._h, self._need(files, "V", "files"), self._need(theta, "Phi", "theta"),
+                                  self._need(V, "V", "V"), _stream_ptr(stream)), "ccdc_map")
 
     # ---- stages (asynchronous on `stream`, default torch's current stream)
     def combine(self, V, Vbar, stream=None):

@@ -11,7 +11,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libccdc.so")
-SOURCES = ["ccdc.hip", "pipeline.hip", "node.hip", "noalloc.hip", "plan.cpp"]
+SOURCES = ["ccdc.hip", "pipeline.hip", "node.hip", "noalloc.hip", "map.hip", "plan.cpp"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 FLAGS = [

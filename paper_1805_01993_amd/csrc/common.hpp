@@ -28,6 +28,7 @@ struct SumF32 {                       // real numbers throughout
     static __device__ __forceinline__ acc add(acc a, acc b) { return a + b; }
     static __device__ __forceinline__ elem code(elem a, elem b) { return a + b; }
     static __device__ __forceinline__ elem uncode(elem a, elem b) { return a - b; }
+    static __device__ __forceinline__ elem gradient(elem theta, elem data) { return theta - data; }
 };
 struct XorU32 {                       // the field F_{2^T} throughout
     using elem = uint32_t;
@@ -40,6 +41,7 @@ struct XorU32 {                       // the field F_{2^T} throughout
     static __device__ __forceinline__ acc add(acc a, acc b) { return a ^ b; }
     static __device__ __forceinline__ elem code(elem a, elem b) { return a ^ b; }
     static __device__ __forceinline__ elem uncode(elem a, elem b) { return a ^ b; }
+    static __device__ __forceinline__ elem gradient(elem theta, elem data) { return theta ^ data; }   // - is XOR in F_{2^T}
 };
 struct HybF32 {                       // numbers are summed, packets are XOR-coded bit patterns (Sec. II)
     using elem = float;
@@ -55,6 +57,7 @@ struct HybF32 {                       // numbers are summed, packets are XOR-cod
         return __uint_as_float(__float_as_uint(a) ^ __float_as_uint(b));
     }
     static __device__ __forceinline__ elem uncode(elem a, elem b) { return code(a, b); }
+    static __device__ __forceinline__ elem gradient(elem theta, elem data) { return theta - data; }
 };
 // The same hybrid for 16-bit floating-point payloads: elements are bit patterns
 // of bfloat16 (BF) or IEEE binary16 numbers, sums are carried in fp32 and
@@ -101,6 +104,8 @@ struct Hyb16 {
     static __device__ __forceinline__ acc add(acc a, acc b) { return a + b; }
     static __device__ __forceinline__ elem code(elem a, elem b) { return (elem)(a ^ b); }
     static __device__ __forceinline__ elem uncode(elem a, elem b) { return (elem)(a ^ b); }
+    // the difference of the two values in fp32 (one rounding), rounded once more to the format
+    static __device__ __forceinline__ elem gradient(elem theta, elem data) { return narrow(widen(theta) - widen(data)); }
 };
 using HybBF16 = Hyb16<true>;
 using HybF16 = Hyb16<false>;
@@ -161,6 +166,12 @@ struct Ops {
 #pragma unroll
         for (int i = 0; i < VEC; i++) a.v[i] = A::uncode(a.v[i], b.v[i]);
         return a;
+    }
+    static __device__ __forceinline__ P gradient(P theta, P data)
+    {
+#pragma unroll
+        for (int i = 0; i < VEC; i++) theta.v[i] = A::gradient(theta.v[i], data.v[i]);
+        return theta;
     }
     static __device__ __forceinline__ P select(bool c, P a, P b)
     {

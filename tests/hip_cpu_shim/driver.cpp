@@ -199,6 +199,43 @@ int main(int argc, char **argv)
     same(X5, X, nx, "node-local X");
     check_phi(Phi5, "node-local Phi");
 
+    // Map stand-in: out = theta - files (XOR in the field), separate buffer and in place
+    {
+        unsigned char *theta = dev(nphi), *out = dev(nv), *inpl = dev(nv);
+        for (int64_t i = 0; i < nphi; i++) std::memcpy(theta + i * eb, V + ((i * 7) % nv) * eb, eb);   // any valid patterns
+        std::memcpy(inpl, V, (size_t)nv * eb);
+        CHECK(ccdc_map(p, V, theta, out, nullptr));
+        CHECK(ccdc_map(p, inpl, theta, inpl, nullptr));
+        same(inpl, out, nv, "map in place");
+        for (int64_t j = 0; j < J; j++)
+            for (int64_t n = 0; n < N; n++)
+                for (int64_t e = 0; e < (int64_t)Q * T; e++) {
+                    const int64_t at = (j * N + n) * Q * T + e, th = j * Q * T + e;
+                    bool ok;
+                    if (half) {
+                        uint16_t a, b, g;
+                        std::memcpy(&a, theta + th * 2, 2);
+                        std::memcpy(&b, V + at * 2, 2);
+                        std::memcpy(&g, out + at * 2, 2);
+                        ok = widen16(g, mode == 3) == widen16(a, mode == 3) - widen16(b, mode == 3);   // small integers: exact
+                    } else if (real) {
+                        float a, b, g;
+                        std::memcpy(&a, theta + th * 4, 4);
+                        std::memcpy(&b, V + at * 4, 4);
+                        std::memcpy(&g, out + at * 4, 4);
+                        ok = g == a - b;
+                    } else {
+                        uint32_t a, b, g;
+                        std::memcpy(&a, theta + th * 4, 4);
+                        std::memcpy(&b, V + at * 4, 4);
+                        std::memcpy(&g, out + at * 4, 4);
+                        ok = g == (a ^ b);
+                    }
+                    if (!ok && bad++ < 5) std::fprintf(stderr, "map: element %lld is wrong\n", (long long)at);
+                }
+        for (unsigned char *q : {theta, out, inpl}) std::free(q);
+    }
+
     ccdc_plan_destroy(p);
     for (unsigned char *q : {V, Vbar, X, D, Phi, X2, D2, Phi2, X3, Phi3, X4, Phi4, X5, Phi5}) std::free(q);
     std::printf("K=%d r=%d Q=%d N=%d T=%lld mode=%d jobs=%d: %ld launches, pipeline %s, %d mismatches\n", K, r, Q, N,

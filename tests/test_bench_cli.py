@@ -31,6 +31,12 @@ def test_algorithmic_bytes():
     assert bench.algorithmic_bytes_pipeline(w5, 512) == 2_089_156_608 + 435_240_960 + 24 * 2048 * 4
     # measured traffic is only quoted for the kernel sources it was measured on
     key = next(iter(bench.TRAFFIC))
-    assert bench.measured_traffic("no such workload", "f32", "pipeline") is None
+    assert bench.measured_traffic("no such workload", "f32", "pipeline") == (None, None)
     t = bench.TRAFFIC[key]
-    assert (bench.measured_traffic(*key) is not None) == (t["source_hash"] == bench.kernel_source_hash())
+    assert (bench.measured_traffic(*key)[0] is not None) == (t["source_hash"] == bench.kernel_source_hash())
+    # every recorded figure names the summary under profiles/ it was taken from
+    for rec in bench.TRAFFIC.values():
+        assert os.path.exists(os.path.join(ROOT, rec["profile"])), rec["profile"]
+    # the default run also reports the other large workloads and the per-node-faithful accounting
+    assert ("cfg5_k24", "f32", "pipeline") in bench.ALSO and ("cfg5_k24", "u32", "pipeline") in bench.ALSO
+    assert ("cfg3_gradient", "f32", "node") in bench.ALSO
