@@ -13,31 +13,36 @@
 namespace {
 using namespace ccdc;
 
+// A workgroup covers kBlock consecutive packs of ONE file (row), so that the file and job
+// indices are wave-uniform and no work item divides.
 template <class A, int VEC>
 __global__ __launch_bounds__(kBlock) void k_map(const typename A::elem *files,      // may be V itself
                                                 const typename A::elem *__restrict__ theta,
-                                                typename A::elem *V, uint64_t job_packs, uint64_t model_packs,
-                                                uint64_t items)
+                                                typename A::elem *V, uint32_t model_packs, uint32_t tiles,
+                                                uint32_t files_per_job)
 {
     using O = Ops<A, VEC>;
     using P = typename O::P;
-    const uint64_t idx = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
-    if (idx >= items) return;
-    const uint64_t job = idx / job_packs, e = (idx - job * job_packs) % model_packs;
-    const P data = load_stream<P>(reinterpret_cast<const P *>(files) + idx);
-    const P model = reinterpret_cast<const P *>(theta)[job * model_packs + e];
-    store_stream(reinterpret_cast<P *>(V) + idx, O::gradient(model, data));
+    const uint32_t row = blockIdx.x / tiles, tile = blockIdx.x - row * tiles;
+    const uint32_t e = tile * kBlock + threadIdx.x;
+    if (e >= model_packs) return;
+    const uint32_t job = row / files_per_job;
+    const size_t at = (size_t)row * model_packs + e;
+    const P data = load_stream<P>(reinterpret_cast<const P *>(files) + at);
+    const P model = reinterpret_cast<const P *>(theta)[(size_t)job * model_packs + e];
+    store_stream(reinterpret_cast<P *>(V) + at, O::gradient(model, data));
 }
 
 template <class A, int VEC>
 int run_map(const ccdc_plan_t *p, const void *files, const void *theta, void *V, hipStream_t st)
 {
     using E = typename A::elem;
-    const uint64_t model_packs = (uint64_t)p->Q * p->T / VEC, job_packs = (uint64_t)p->N * model_packs;
-    const uint64_t items = (uint64_t)p->J * job_packs;
-    if (!fits_launch((items + kBlock - 1) / kBlock)) return CCDC_ESIZE;
-    k_map<A, VEC><<<(uint32_t)((items + kBlock - 1) / kBlock), kBlock, 0, st>>>((const E *)files, (const E *)theta, (E *)V,
-                                                                                 job_packs, model_packs, items);
+    const uint64_t model_packs = (uint64_t)p->Q * p->T / VEC, rows = (uint64_t)p->J * p->N;
+    if (!fits_launch(model_packs)) return CCDC_ESIZE;
+    const uint64_t tiles = (model_packs + kBlock - 1) / kBlock;
+    if (!fits_launch(rows * tiles)) return CCDC_ESIZE;
+    k_map<A, VEC><<<(uint32_t)(rows * tiles), kBlock, 0, st>>>((const E *)files, (const E *)theta, (E *)V,
+                                                                (uint32_t)model_packs, (uint32_t)tiles, (uint32_t)p->N);
     return launched();
 }
 
