@@ -45,41 +45,60 @@ ALSO = [
 # is recorded with them; for any other source `traffic` is null.
 TRAFFIC = {
     ("cfg3_gradient", "f32", "pipeline"): {
-        "source_hash": "ee5b64d2e4c83840", "fetch_kib": 1420044.6, "write_kib": 1150002.4, "fetch_scale": 2.0, "write_scale": 1.0,
+        "source_hash": "5ae5973f07537e1f", "fetch_kib": 1420598.0, "write_kib": 1150000.4, "fetch_scale": 2.0, "write_scale": 1.0,
         "profile": "profiles/pipeline_fused_cfg3_gradient_f32.md"},
     ("cfg5_k24", "f32", "pipeline"): {
-        "source_hash": "ee5b64d2e4c83840", "fetch_kib": 1043874.8, "write_kib": 462096.0, "fetch_scale": 2.0, "write_scale": 1.0,
+        "source_hash": "5ae5973f07537e1f", "fetch_kib": 1043903.3, "write_kib": 462096.0, "fetch_scale": 2.0, "write_scale": 1.0,
         "profile": "profiles/pipeline_fused_cfg5_k24_f32.md"},
     ("cfg5_k24", "u32", "pipeline"): {
-        "source_hash": "ee5b64d2e4c83840", "fetch_kib": 1043710.6, "write_kib": 462096.0, "fetch_scale": 2.0, "write_scale": 1.0,
+        "source_hash": "5ae5973f07537e1f", "fetch_kib": 1043688.9, "write_kib": 462096.0, "fetch_scale": 2.0, "write_scale": 1.0,
         "profile": "profiles/pipeline_fused_cfg5_k24_u32.md"},
     ("cfg3_gradient", "bf16", "pipeline"): {
-        "source_hash": "ee5b64d2e4c83840", "fetch_kib": 707281.8, "write_kib": 575001.3, "fetch_scale": 2.0, "write_scale": 1.0,
+        "source_hash": "5ae5973f07537e1f", "fetch_kib": 707225.7, "write_kib": 575002.2, "fetch_scale": 2.0, "write_scale": 1.0,
         "profile": "profiles/pipeline_fused_cfg3_gradient_bf16.md"},
     ("cfg5_k24", "bf16", "pipeline"): {
-        "source_hash": "ee5b64d2e4c83840", "fetch_kib": 531552.3, "write_kib": 249480.0, "fetch_scale": 2.0, "write_scale": 1.0,
+        "source_hash": "5ae5973f07537e1f", "fetch_kib": 531552.8, "write_kib": 249480.0, "fetch_scale": 2.0, "write_scale": 1.0,
         "profile": "profiles/pipeline_fused_cfg5_k24_bf16.md"},
     ("cfg3_gradient", "f32", "shuffle+reduce"): {
-        "source_hash": "ee5b64d2e4c83840", "fetch_kib": 1050026.9, "write_kib": 3150268.6, "fetch_scale": 2.0, "write_scale": 1.0,
+        "source_hash": "434fac2d52a1a266", "fetch_kib": 1050027.0, "write_kib": 3150292.3, "fetch_scale": 2.0, "write_scale": 1.0,
         "profile": "profiles/shuffle_fused_reduce_cfg3_gradient_f32.md"},
     ("jobs_k8", "f32", "shuffle+reduce"): {
-        "source_hash": "ee5b64d2e4c83840", "fetch_kib": 909406.7, "write_kib": 892538.2, "fetch_scale": 2.0, "write_scale": 1.0,
+        "source_hash": "434fac2d52a1a266", "fetch_kib": 909477.9, "write_kib": 892629.6, "fetch_scale": 2.0, "write_scale": 1.0,
         "profile": "profiles/shuffle_fused_reduce_jobs_k8_f32.md"},
     ("comp_gradient", "f32", "combine+reduce"): {
-        "source_hash": "ee5b64d2e4c83840", "fetch_kib": 1050013.8, "write_kib": 300000.0, "fetch_scale": 2.0, "write_scale": 1.0,
+        "source_hash": "434fac2d52a1a266", "fetch_kib": 1050013.6, "write_kib": 300000.0, "fetch_scale": 2.0, "write_scale": 1.0,
         "profile": "profiles/combine_reduce_comp_gradient_f32.md"},
     ("cfg3_gradient", "f32", "node"): {
-        "source_hash": "ee5b64d2e4c83840", "fetch_kib": 2450059.8, "write_kib": 100000.0, "fetch_scale": 2.0, "write_scale": 1.0,
+        "source_hash": "4e60cca33d8a5867", "fetch_kib": 2450065.3, "write_kib": 100000.0, "fetch_scale": 2.0, "write_scale": 1.0,
         "profile": "profiles/node_encode_decode_reduce_cfg3_gradient_f32.md"},
+    ("cfg3_gradient", "f32", "map+pipeline"): {
+        "source_hash": "0102761739fd1022", "fetch_kib": 1450012.0, "write_kib": 2800000.4, "fetch_scale": 2.0, "write_scale": 1.0,
+        "profile": "profiles/map_pipeline_fused_cfg3_gradient_f32.md"},
+    ("cfg2_k10", "f32", "pipeline"): {
+        "source_hash": "5ae5973f07537e1f", "fetch_kib": 11102.3, "write_kib": 7095.9, "fetch_scale": 2.0, "write_scale": 1.0,
+        "profile": "profiles/pipeline_fused_cfg2_k10_f32.md"},
+    ("cfg4_k16", "f32", "pipeline"): {
+        "source_hash": "5ae5973f07537e1f", "fetch_kib": 84071.4, "write_kib": 58340.7, "fetch_scale": 2.0, "write_scale": 1.0,
+        "profile": "profiles/pipeline_fused_cfg4_k16_f32.md"},
 }
 
 
-def kernel_source_hash():
-    import glob
+# Sources that define the kernels and the launch geometry of each path: a recorded traffic
+# figure holds as long as these files are what they were when it was recorded.
+PATH_SOURCES = {
+    "pipeline": ["pipeline.hip", "common.hpp", "plan.hpp", "plan.cpp"],
+    "shuffle+reduce": ["ccdc.hip", "common.hpp", "plan.hpp", "plan.cpp"],
+    "combine+reduce": ["ccdc.hip", "common.hpp", "plan.hpp", "plan.cpp"],
+    "node": ["node.hip", "common.hpp", "plan.hpp", "plan.cpp"],
+    "map+pipeline": ["map.hip", "pipeline.hip", "common.hpp", "plan.hpp", "plan.cpp"],
+}
+
+
+def kernel_source_hash(path):
     import hashlib
     h = hashlib.sha256()
-    for f in sorted(glob.glob(os.path.join(ROOT, "paper_1805_01993_amd", "csrc", "*"))):
-        with open(f, "rb") as fh:
+    for f in PATH_SOURCES[path]:
+        with open(os.path.join(ROOT, "paper_1805_01993_amd", "csrc", f), "rb") as fh:
             h.update(fh.read())
     return h.hexdigest()[:16]
 
@@ -87,7 +106,7 @@ def kernel_source_hash():
 def measured_traffic(workload, mode, path):
     """(bytes, where they were recorded) or (None, None) when the sources have changed since."""
     t = TRAFFIC.get((workload, mode, path))
-    if not t or t["source_hash"] != kernel_source_hash():
+    if not t or t["source_hash"] != kernel_source_hash(path):
         return None, None
     return int(1024 * (t["fetch_kib"] * t["fetch_scale"] + t["write_kib"] * t["write_scale"])), t["profile"]
 

@@ -13,17 +13,24 @@
 namespace {
 using namespace ccdc;
 
-// A workgroup covers kBlock consecutive packs of ONE file (row), so that the file and job
-// indices are wave-uniform and no work item divides.
+// A workgroup covers kBlock consecutive packs (a tile) of ONE file (row), so that the file
+// and job indices are wave-uniform and no work item divides.  Workgroups are ordered
+// (group of kMapGroup tiles, file, tile in the group): the piece of theta a group covers
+// (1 MiB) is used by every file before the next piece is touched, so it is fetched from
+// HBM once and re-read from cache, while every file is still read in runs of 1 MiB.
+constexpr uint32_t kMapGroup = 256;
 template <class A, int VEC>
 __global__ __launch_bounds__(kBlock) void k_map(const typename A::elem *files,      // may be V itself
                                                 const typename A::elem *__restrict__ theta,
                                                 typename A::elem *V, uint32_t model_packs, uint32_t tiles,
-                                                uint32_t files_per_job)
+                                                uint32_t rows, uint32_t files_per_job)
 {
     using O = Ops<A, VEC>;
     using P = typename O::P;
-    const uint32_t row = blockIdx.x / tiles, tile = blockIdx.x - row * tiles;
+    const uint32_t per_group = rows * kMapGroup;
+    const uint32_t group = blockIdx.x / per_group, in_group = blockIdx.x - group * per_group;
+    const uint32_t row = in_group / kMapGroup, tile = group * kMapGroup + (in_group - row * kMapGroup);
+    if (tile >= tiles) return;                        // the last group may be short
     const uint32_t e = tile * kBlock + threadIdx.x;
     if (e >= model_packs) return;
     const uint32_t job = row / files_per_job;
@@ -39,10 +46,10 @@ int run_map(const ccdc_plan_t *p, const void *files, const void *theta, void *V,
     using E = typename A::elem;
     const uint64_t model_packs = (uint64_t)p->Q * p->T / VEC, rows = (uint64_t)p->J * p->N;
     if (!fits_launch(model_packs)) return CCDC_ESIZE;
-    const uint64_t tiles = (model_packs + kBlock - 1) / kBlock;
-    if (!fits_launch(rows * tiles)) return CCDC_ESIZE;
-    k_map<A, VEC><<<(uint32_t)(rows * tiles), kBlock, 0, st>>>((const E *)files, (const E *)theta, (E *)V,
-                                                                (uint32_t)model_packs, (uint32_t)tiles, (uint32_t)p->N);
+    const uint64_t tiles = (model_packs + kBlock - 1) / kBlock, groups = (tiles + kMapGroup - 1) / kMapGroup;
+    if (!fits_launch(rows * groups * kMapGroup)) return CCDC_ESIZE;
+    k_map<A, VEC><<<(uint32_t)(rows * groups * kMapGroup), kBlock, 0, st>>>(
+        (const E *)files, (const E *)theta, (E *)V, (uint32_t)model_packs, (uint32_t)tiles, (uint32_t)rows, (uint32_t)p->N);
     return launched();
 }
 

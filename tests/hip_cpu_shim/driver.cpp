@@ -169,6 +169,18 @@ int main(int argc, char **argv)
         }
     };
 
+    // SHIM_ONLY_PIPELINE=1: only the one-pass pipeline, checked against the plain sum (for shapes
+    // at which the staged kernels, one emulated thread per work item, would take too long)
+    if (std::getenv("SHIM_ONLY_PIPELINE")) {
+        CHECK(ccdc_pipeline_fused(p, V, X3, Phi3, nullptr));
+        check_phi(Phi3, "pipeline Phi");
+        ccdc_plan_destroy(p);
+        for (unsigned char *q : {V, Vbar, X, D, Phi, X2, D2, Phi2, X3, Phi3, X4, Phi4, X5, Phi5}) std::free(q);
+        std::printf("K=%d r=%d Q=%d N=%d T=%lld mode=%d: pipeline only, %ld launches, %d mismatches\n", K, r, Q, N,
+                    (long long)T, mode, shim::launches.load(), bad);
+        std::fflush(stdout);
+        return bad ? 1 : 0;
+    }
     CHECK(ccdc_combine(p, V, Vbar, nullptr));
     CHECK(ccdc_encode(p, Vbar, X, nullptr));
     CHECK(ccdc_decode(p, X, Vbar, D, nullptr));

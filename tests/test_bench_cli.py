@@ -33,7 +33,7 @@ def test_algorithmic_bytes():
     key = next(iter(bench.TRAFFIC))
     assert bench.measured_traffic("no such workload", "f32", "pipeline") == (None, None)
     t = bench.TRAFFIC[key]
-    assert (bench.measured_traffic(*key)[0] is not None) == (t["source_hash"] == bench.kernel_source_hash())
+    assert (bench.measured_traffic(*key)[0] is not None) == (t["source_hash"] == bench.kernel_source_hash(key[2]))
     # every recorded figure names the summary under profiles/ it was taken from
     for rec in bench.TRAFFIC.values():
         assert os.path.exists(os.path.join(ROOT, rec["profile"])), rec["profile"]
