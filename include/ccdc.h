@@ -40,9 +40,10 @@
  * surface at the caller's next synchronisation.  The calls that keep partial
  * sums in the plan's workspace (ccdc_reduce, ccdc_pipeline_fused,
  * ccdc_node_decode_reduce) are put in order by the library when they come on
- * different streams or host threads: the later call's stream waits for the
- * earlier call's kernels.  A stream under graph capture is not ordered this way;
- * replay such a graph apart from other work on the same plan.
+ * different streams or host threads: the later call's stream waits for what the
+ * earlier call's stream had been given (keep that stream alive until then).  A
+ * stream under graph capture is not ordered this way; replay such a graph apart
+ * from other work on the same plan.
  */
 #ifndef CCDC_H
 #define CCDC_H

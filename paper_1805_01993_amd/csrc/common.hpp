@@ -320,11 +320,15 @@ inline int launched()
 
 // The plan's workspace holds partial sums between the two kernels of one call.
 // Calls that use it are put in order also when they come on different streams:
-// each records the plan's event once its kernels are enqueued, and a call on
-// another stream first makes its stream wait for that event.  Host threads
-// take turns through the plan's mutex.  A stream under graph capture is left
-// alone (an event recorded outside a capture cannot be waited for inside one):
-// whoever replays the graph keeps it apart from other users of the plan.
+// the plan remembers the stream of the last such call, and a call that arrives
+// on another stream first records the plan's event at the tail of that earlier
+// stream and makes its own stream wait for it (so it waits for everything the
+// earlier stream had been given, the earlier call included).  Calls that stay
+// on one stream, the usual case, add no event and no wait.  Host threads take
+// turns through the plan's mutex.  A stream under graph capture is left alone
+// and forgotten (an event recorded outside a capture cannot be waited for
+// inside one): whoever replays the graph keeps it apart from other users of
+// the plan.  The earlier stream must still exist when the later call comes.
 class WorkspaceOrder {
 public:
     WorkspaceOrder(const ccdc_plan_t *p, hipStream_t st, bool uses_workspace)
@@ -339,19 +343,20 @@ public:
             on_ = false;
             return;
         }
-        if (p_->ws_used && p_->ws_stream != (void *)st_ &&
-            hipStreamWaitEvent(st_, (hipEvent_t)p_->ws_event, 0) != hipSuccess)
-            (void)hipGetLastError();
+        if (p_->ws_used && p_->ws_stream != (void *)st_) {
+            hipEvent_t ev = (hipEvent_t)p_->ws_event;
+            hipStream_t earlier = (hipStream_t)p_->ws_stream;
+            hipStreamCaptureStatus es = hipStreamCaptureStatusNone;       // nothing is recorded into someone's capture
+            if (hipStreamIsCapturing(earlier, &es) != hipSuccess || es != hipStreamCaptureStatusNone ||
+                hipEventRecord(ev, earlier) != hipSuccess || hipStreamWaitEvent(st_, ev, 0) != hipSuccess)
+                (void)hipGetLastError();
+        }
     }
     ~WorkspaceOrder()
     {
         if (!on_) return;
-        if (hipEventRecord((hipEvent_t)p_->ws_event, st_) == hipSuccess) {
-            p_->ws_used = true;
-            p_->ws_stream = (void *)st_;
-        } else {
-            (void)hipGetLastError();
-        }
+        p_->ws_used = true;
+        p_->ws_stream = (void *)st_;
         p_->ws_mutex.unlock();
     }
     WorkspaceOrder(const WorkspaceOrder &) = delete;
