@@ -307,6 +307,9 @@ def main():
                     help="time only the workload named (the default run also times the other large workloads "
                          "and accountings and reports them under the key \"also\")")
     ap.add_argument("--cpu-sample-T", type=int, default=0)
+    ap.add_argument("--stream-ceilings", action="store_true",
+                    help="run only plain streaming kernels of the array library (fill, copy, add, addcmul on 0.5 GiB "
+                         "operands) and print what each sustains: context for the roofline fractions")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a plain device copy of known size (1 GiB read + 1 GiB written per launch): "
                          "what FETCH_SIZE / WRITE_SIZE read for it scales the counters of the other kernels")
@@ -327,6 +330,31 @@ def main():
         sys.exit(1)
     torch.cuda.set_device(0)
     L.load_library()
+
+    if args.stream_ceilings:
+        n = 1 << 27                                   # 2^27 fp32 = 0.5 GiB per operand
+        a, b, c, d = (torch.full((n,), float(i + 1), dtype=torch.float32, device="cuda") for i in range(4))
+        ops = [("fill: 0 reads, 1 write", 1, lambda: d.fill_(1.0)),
+               ("copy: 1 read, 1 write", 2, lambda: d.copy_(a)),
+               ("add: 2 reads, 1 write", 3, lambda: torch.add(a, b, out=d)),
+               ("addcmul: 3 reads, 1 write", 4, lambda: torch.addcmul(a, b, c, out=d)),
+               ("sum: 1 read, 0 writes", 1, lambda: a.sum())]
+        res = {}
+        for name, streams, fn in ops:
+            for _ in range(args.warmup):
+                fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(args.steps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / args.steps
+            res[name] = {"ms": round(ms, 4), "GB/s": round(streams * 4 * n / ms / 1e6, 1),
+                         "frac_of_peak": round(streams * 4 * n / ms / 1e6 / HBM_PEAK_GBPS, 4)}
+        print(json.dumps({"stream_ceilings": res, "operand_bytes": 4 * n, "steps": args.steps}), flush=True)
+        return
 
     if args.calibrate_copy:
         n = 1 << 28                                   # 2^28 fp32 = 1 GiB

@@ -226,13 +226,17 @@ int ccdc_decode(const ccdc_plan_t *plan, const void *X, const void *Vbar, void *
  * sum is split. */
 int ccdc_reduce(const ccdc_plan_t *plan, const void *V, const void *D, void *Phi, void *stream);
 
-/* combine + encode + decode in one pass: every needed element of V is read
- * once, X and D are written; Vbar is never materialised.  Results equal the
- * three separate calls (bit-exact in XOR mode; same operation order in fp32). */
+/* The three shuffle steps of Sec. IV-B (pre-combining, the coded-packet equation,
+ * the decoding paragraph) in one pass: every needed element of V is read once, X
+ * and D are written; Vbar is never materialised.  A coded pack is decoded for each
+ * of its r receivers as in ccdc_decode, from the packs of the OTHER packets in it.
+ * Results equal the three separate calls (bit-exact in XOR mode; same operation
+ * order in fp32). */
 int ccdc_shuffle_fused(const ccdc_plan_t *plan, const void *V, void *X, void *D, void *stream);
 
-/* The whole path in one pass for single-job plans (ccdc_plan): combine, encode,
- * decode and reduce; every element of V is read once, X and Phi are written,
+/* The whole path of Sec. IV-B in one pass for single-job plans (ccdc_plan):
+ * pre-combining, the coded-packet equation, the decoding paragraph and the final
+ * reduction of its last paragraphs; every element of V is read once, X and Phi are written,
  * neither Vbar nor D is materialised.  Each coded pack is decoded for each
  * receiver as in ccdc_decode (coded pack minus the receiver's side information)
  * and added to that receiver's output, together with the files it stores itself.
