@@ -36,6 +36,8 @@ def test_replays_equal_eager(torch, L, K, r, Q, N, T, mode):
     V = inputs[0].clone()
     new = lambda key: torch.zeros(sh[key], dtype=V.dtype, device="cuda")
     X, D, Phi, Xp, Php, Xn, Phn = new("X"), new("D"), new("Phi"), new("X"), new("Phi"), new("X"), new("Phi")
+    Xs, Phs, Vm, Phm = new("X"), new("Phi"), new("V"), new("Phi")
+    theta = generate_torch(1, 1, Q, T, 9, kind, device="cuda")[:, 0].contiguous()
 
     def enqueue(stream):
         plan.shuffle_fused(V, X, D, stream=stream)
@@ -43,8 +45,11 @@ def test_replays_equal_eager(torch, L, K, r, Q, N, T, mode):
         plan.pipeline_fused(V, Xp, Php, stream=stream)
         plan.node_encode(-1, V, Xn, stream=stream)
         plan.node_decode_reduce(-1, V, Xn, Phn, stream=stream)
+        plan.pipeline_fused_noalloc(V, Xs, Phs, stream=stream)      # the entry point meant for captured code
+        plan.map(V, theta, Vm, stream=stream)                       # a step that starts from files
+        plan.pipeline_fused_noalloc(Vm, Xs, Phm, stream=stream)
 
-    outs = (X, D, Phi, Xp, Php, Xn, Phn)
+    outs = (X, D, Phi, Xp, Php, Xn, Phn, Phs, Vm, Phm)
     bits = lambda t: t.view(torch.int16 if t.element_size() == 2 else torch.int32)
     eager = []
     for inp in inputs:
