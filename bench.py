@@ -45,40 +45,40 @@ ALSO = [
 # is recorded with them; for any other source `traffic` is null.
 TRAFFIC = {
     ("cfg3_gradient", "f32", "pipeline"): {
-        "source_hash": "5ae5973f07537e1f", "fetch_kib": 1420598.0, "write_kib": 1150000.4, "fetch_scale": 2.0, "write_scale": 1.0,
+        "source_hash": "4db11b3dcfbb938c", "fetch_kib": 1420211.0, "write_kib": 1150001.2, "fetch_scale": 2.0, "write_scale": 1.0,
         "profile": "profiles/pipeline_fused_cfg3_gradient_f32.md"},
     ("cfg5_k24", "f32", "pipeline"): {
-        "source_hash": "5ae5973f07537e1f", "fetch_kib": 1043903.3, "write_kib": 462096.0, "fetch_scale": 2.0, "write_scale": 1.0,
+        "source_hash": "4db11b3dcfbb938c", "fetch_kib": 1043920.8, "write_kib": 462096.0, "fetch_scale": 2.0, "write_scale": 1.0,
         "profile": "profiles/pipeline_fused_cfg5_k24_f32.md"},
     ("cfg5_k24", "u32", "pipeline"): {
-        "source_hash": "5ae5973f07537e1f", "fetch_kib": 1043688.9, "write_kib": 462096.0, "fetch_scale": 2.0, "write_scale": 1.0,
+        "source_hash": "4db11b3dcfbb938c", "fetch_kib": 1043699.0, "write_kib": 462096.0, "fetch_scale": 2.0, "write_scale": 1.0,
         "profile": "profiles/pipeline_fused_cfg5_k24_u32.md"},
     ("cfg3_gradient", "bf16", "pipeline"): {
-        "source_hash": "5ae5973f07537e1f", "fetch_kib": 707225.7, "write_kib": 575002.2, "fetch_scale": 2.0, "write_scale": 1.0,
+        "source_hash": "4db11b3dcfbb938c", "fetch_kib": 707511.3, "write_kib": 575002.7, "fetch_scale": 2.0, "write_scale": 1.0,
         "profile": "profiles/pipeline_fused_cfg3_gradient_bf16.md"},
     ("cfg5_k24", "bf16", "pipeline"): {
-        "source_hash": "5ae5973f07537e1f", "fetch_kib": 531552.8, "write_kib": 249480.0, "fetch_scale": 2.0, "write_scale": 1.0,
+        "source_hash": "4db11b3dcfbb938c", "fetch_kib": 531565.0, "write_kib": 249480.0, "fetch_scale": 2.0, "write_scale": 1.0,
         "profile": "profiles/pipeline_fused_cfg5_k24_bf16.md"},
     ("cfg3_gradient", "f32", "shuffle+reduce"): {
-        "source_hash": "434fac2d52a1a266", "fetch_kib": 1050027.0, "write_kib": 3150292.3, "fetch_scale": 2.0, "write_scale": 1.0,
+        "source_hash": "0042e45ec8b03434", "fetch_kib": 1050027.0, "write_kib": 3150143.1, "fetch_scale": 2.0, "write_scale": 1.0,
         "profile": "profiles/shuffle_fused_reduce_cfg3_gradient_f32.md"},
     ("jobs_k8", "f32", "shuffle+reduce"): {
-        "source_hash": "434fac2d52a1a266", "fetch_kib": 909477.9, "write_kib": 892629.6, "fetch_scale": 2.0, "write_scale": 1.0,
+        "source_hash": "0042e45ec8b03434", "fetch_kib": 909229.5, "write_kib": 892409.5, "fetch_scale": 2.0, "write_scale": 1.0,
         "profile": "profiles/shuffle_fused_reduce_jobs_k8_f32.md"},
     ("comp_gradient", "f32", "combine+reduce"): {
-        "source_hash": "434fac2d52a1a266", "fetch_kib": 1050013.6, "write_kib": 300000.0, "fetch_scale": 2.0, "write_scale": 1.0,
+        "source_hash": "0042e45ec8b03434", "fetch_kib": 1050013.6, "write_kib": 300000.0, "fetch_scale": 2.0, "write_scale": 1.0,
         "profile": "profiles/combine_reduce_comp_gradient_f32.md"},
     ("cfg3_gradient", "f32", "node"): {
-        "source_hash": "4e60cca33d8a5867", "fetch_kib": 2450065.3, "write_kib": 100000.0, "fetch_scale": 2.0, "write_scale": 1.0,
+        "source_hash": "a1f343c54b1ee29f", "fetch_kib": 2450065.2, "write_kib": 100000.0, "fetch_scale": 2.0, "write_scale": 1.0,
         "profile": "profiles/node_encode_decode_reduce_cfg3_gradient_f32.md"},
     ("cfg3_gradient", "f32", "map+pipeline"): {
-        "source_hash": "0102761739fd1022", "fetch_kib": 1450012.0, "write_kib": 2800000.4, "fetch_scale": 2.0, "write_scale": 1.0,
+        "source_hash": "689605039fbfef14", "fetch_kib": 1450012.0, "write_kib": 2800000.2, "fetch_scale": 2.0, "write_scale": 1.0,
         "profile": "profiles/map_pipeline_fused_cfg3_gradient_f32.md"},
     ("cfg2_k10", "f32", "pipeline"): {
-        "source_hash": "5ae5973f07537e1f", "fetch_kib": 11102.3, "write_kib": 7095.9, "fetch_scale": 2.0, "write_scale": 1.0,
+        "source_hash": "4db11b3dcfbb938c", "fetch_kib": 11102.3, "write_kib": 7095.8, "fetch_scale": 2.0, "write_scale": 1.0,
         "profile": "profiles/pipeline_fused_cfg2_k10_f32.md"},
     ("cfg4_k16", "f32", "pipeline"): {
-        "source_hash": "5ae5973f07537e1f", "fetch_kib": 84071.4, "write_kib": 58340.7, "fetch_scale": 2.0, "write_scale": 1.0,
+        "source_hash": "4db11b3dcfbb938c", "fetch_kib": 83533.5, "write_kib": 58254.9, "fetch_scale": 2.0, "write_scale": 1.0,
         "profile": "profiles/pipeline_fused_cfg4_k16_f32.md"},
 }
 
