@@ -3,14 +3,14 @@
 // index arithmetic of the kernels and launchers (global memory, LDS, grids) can be bounds-checked
 // on a CPU; the product never uses it.
 //
-// Model: a launch runs its workgroups one after the other; the threads of a workgroup are real
-// threads (one per lane) that meet at __syncthreads() through a barrier; device memory is host heap
-// (so every hipMalloc'd buffer has sanitizer red zones); dynamic LDS is a fresh heap block per
-// workgroup; streams and events do nothing (everything is synchronous).
+// Model: the lanes of a workgroup are real threads (one per lane, kept for a whole launch) that
+// walk the workgroups in order and meet only where the kernel synchronises (__syncthreads, lane
+// shuffles); device memory is host heap (so every hipMalloc'd buffer has sanitizer red zones);
+// dynamic LDS and a kernel's static __shared__ array are fresh heap blocks per workgroup; streams
+// and events do nothing (a launch returns when all its workgroups are done).
 #pragma once
 
 #include <atomic>
-#include <barrier>
 #include <condition_variable>
 #include <cstddef>
 #include <cstdint>
@@ -28,7 +28,6 @@
 #define __forceinline__ inline __attribute__((always_inline))
 #define __launch_bounds__(...)
 #define __align__(n) __attribute__((aligned(n)))
-#define __shared__ static
 #define HIP_SYMBOL(x) (&(x))
 
 struct dim3 {
@@ -57,6 +56,7 @@ extern int blocks_per_cu;                               // what the occupancy qu
 extern size_t max_dynamic_lds;                          // launches asking for more are refused
 extern std::atomic<long> launches;
 void barrier_wait();                                    // __syncthreads()
+void *block_static(size_t bytes);                       // the running workgroup's static __shared__ array
 uint32_t shuffle_xor(uint32_t v, int mask);             // all lanes of the workgroup call it together
 void launch(dim3 grid, dim3 block, size_t lds, const std::function<void()> &body);
 }  // namespace shim

@@ -1,6 +1,7 @@
 // Runtime of the host stand-in for HIP (see hip/hip_runtime.h).  Test infrastructure only.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstdio>
 
 thread_local shim_uint3 threadIdx, blockIdx;
@@ -14,28 +15,71 @@ size_t max_dynamic_lds = 64 * 1024;
 std::atomic<long> launches{0};
 
 namespace {
-// the threads of the workgroup that is running (a launch runs its workgroups in turn)
-struct Team {
-    std::unique_ptr<std::barrier<>> bar;
-    std::vector<uint32_t> exchange;
-    int lanes = 0;
+// State of one workgroup of the running launch.  The lanes (one OS thread each, kept for the
+// whole launch) walk the workgroups in order but NOT in step: a lane only waits for the other
+// lanes of its workgroup where the kernel itself synchronises (__syncthreads, lane shuffles), so
+// kernels without barriers cost no system calls per workgroup.  A lane that has returned from
+// the kernel counts as arrived at every later barrier of that workgroup.
+struct Block {
+    std::mutex m;
+    std::condition_variable cv;
+    int waiting = 0, done = 0;
+    unsigned long generation = 0;
+    unsigned char *smem = nullptr;        // dynamic LDS, made by the first lane that gets here
+    void *statics = nullptr;              // the kernel's static __shared__ array, if it has one
+    std::vector<uint32_t> exchange;       // lane shuffles
 };
-Team team;
-thread_local bool left_team = false;
+struct Launch {
+    std::unique_ptr<Block[]> blocks;
+    int lanes = 0;
+    size_t lds = 0;
+};
+Launch cur;
+thread_local Block *my_block = nullptr;
 int last_error = hipSuccess;
+constexpr unsigned kWindow = 32;          // a lane runs at most this many workgroups ahead of the slowest
 }  // namespace
 
-void barrier_wait() { team.bar->arrive_and_wait(); }
+void barrier_wait()
+{
+    Block &b = *my_block;
+    std::unique_lock<std::mutex> lock(b.m);
+    if (++b.waiting + b.done == cur.lanes) {
+        b.waiting = 0;
+        b.generation++;
+        b.cv.notify_all();
+    } else {
+        const unsigned long g = b.generation;
+        b.cv.wait(lock, [&] { return b.generation != g; });
+    }
+}
 
 uint32_t shuffle_xor(uint32_t v, int mask)
 {
+    Block &b = *my_block;
     const int lane = (int)threadIdx.x;
-    team.exchange[lane] = v;
-    team.bar->arrive_and_wait();
+    {
+        std::lock_guard<std::mutex> lock(b.m);
+        if (b.exchange.empty()) b.exchange.assign(cur.lanes, 0);
+        b.exchange[lane] = v;
+    }
+    barrier_wait();
     const int src = lane ^ mask;
-    const uint32_t got = src < team.lanes ? team.exchange[src] : v;
-    team.bar->arrive_and_wait();
+    uint32_t got = v;
+    {
+        std::lock_guard<std::mutex> lock(b.m);
+        if (src < cur.lanes) got = b.exchange[src];
+    }
+    barrier_wait();
     return got;
+}
+
+void *block_static(size_t bytes)
+{
+    Block &b = *my_block;
+    std::lock_guard<std::mutex> lock(b.m);
+    if (!b.statics) b.statics = std::malloc(bytes);
+    return b.statics;
 }
 
 void launch(dim3 grid, dim3 block, size_t lds, const std::function<void()> &body)
@@ -46,20 +90,12 @@ void launch(dim3 grid, dim3 block, size_t lds, const std::function<void()> &body
         last_error = hipErrorInvalidValue;
         return;
     }
-    // One thread per lane, kept for the whole launch; the workgroups run one after the other.
-    // team.bar serves __syncthreads() inside a workgroup (a lane that has returned drops out
-    // of it); between_blocks keeps the lanes together from one workgroup to the next.
     const int n = (int)block.x;
-    std::barrier<> between_blocks(n);
-    unsigned char *smem = nullptr;
-    auto new_block = [&] {
-        std::free(smem);
-        smem = lds ? static_cast<unsigned char *>(std::malloc(lds)) : nullptr;
-        team.bar = std::make_unique<std::barrier<>>(n);
-    };
-    team.exchange.assign(n, 0);
-    team.lanes = n;
-    new_block();
+    cur.blocks.reset(new Block[grid.x]);
+    cur.lanes = n;
+    cur.lds = lds;
+    std::vector<std::atomic<unsigned>> progress(n);
+    for (auto &p : progress) p.store(0);
     std::vector<std::thread> pool;
     pool.reserve(n);
     for (int t = 0; t < n; t++)
@@ -67,18 +103,43 @@ void launch(dim3 grid, dim3 block, size_t lds, const std::function<void()> &body
             blockDim = block;
             gridDim = grid;
             for (unsigned b = 0; b < grid.x; b++) {
+                if (b >= kWindow && b % 8 == 0) {       // bound the memory of workgroups in progress
+                    for (;;) {
+                        unsigned slowest = b;
+                        for (auto &p : progress) slowest = std::min(slowest, p.load(std::memory_order_relaxed));
+                        if (slowest + kWindow > b) break;
+                        std::this_thread::yield();
+                    }
+                }
+                Block &blk = cur.blocks[b];
+                my_block = &blk;
                 threadIdx = {(unsigned)t, 0, 0};
                 blockIdx = {b, 0, 0};
-                dyn_smem = smem;
+                dyn_smem = nullptr;
+                if (lds) {
+                    std::lock_guard<std::mutex> lock(blk.m);
+                    if (!blk.smem) blk.smem = static_cast<unsigned char *>(std::malloc(lds));
+                    dyn_smem = blk.smem;
+                }
                 body();
-                team.bar->arrive_and_drop();            // a lane that is done no longer holds up the others
-                between_blocks.arrive_and_wait();
-                if (t == 0 && b + 1 < grid.x) new_block();
-                between_blocks.arrive_and_wait();
+                {
+                    std::lock_guard<std::mutex> lock(blk.m);
+                    if (++blk.done == n) {                // last lane out frees the workgroup's memory
+                        std::free(blk.smem);
+                        std::free(blk.statics);
+                        blk.smem = nullptr;
+                        blk.statics = nullptr;
+                    } else if (blk.waiting > 0 && blk.waiting + blk.done == n) {
+                        blk.waiting = 0;                  // the others were waiting for this lane only
+                        blk.generation++;
+                        blk.cv.notify_all();
+                    }
+                }
+                progress[t].store(b + 1, std::memory_order_relaxed);
             }
         });
     for (auto &th : pool) th.join();
-    std::free(smem);
+    cur.blocks.reset();
 }
 }  // namespace shim
 

@@ -1,9 +1,10 @@
 """Rewrite HIP sources so that a host C++ compiler accepts them (test infrastructure only).
 
-Two constructs have no host spelling: the triple-chevron launch and the dynamic LDS
-declaration.  `K<<<grid, block, lds, stream>>>(args);` becomes
-`shim::launch(grid, block, lds, [&] { K(args); });` and
-`extern __shared__ ... name[];` becomes `unsigned char *name = shim::dyn_smem;`.
+Three constructs have no host spelling: the triple-chevron launch and the two LDS
+declarations.  `K<<<grid, block, lds, stream>>>(args);` becomes
+`shim::launch(grid, block, lds, [&] { K(args); });`,
+`extern __shared__ ... name[];` becomes `unsigned char *name = shim::dyn_smem;` and
+`__shared__ T name[N];` becomes a per-workgroup heap block, `T *name = ...block_static(...)`.
 Everything else compiles as it stands against hip_cpu_shim/hip/hip_runtime.h."""
 import re
 import sys
@@ -59,6 +60,8 @@ def _split_top(s):
 
 def translate(text):
     text = re.sub(r"extern\s+__shared__[^;]*?\b(\w+)\[\];", r"unsigned char *\1 = shim::dyn_smem;", text)
+    text = re.sub(r"(?<!extern )__shared__\s+([\w:<>]+)\s+(\w+)\[([^\]]+)\];",
+                  r"\1 *\2 = static_cast<\1 *>(shim::block_static(sizeof(\1) * (\3)));", text)
     out, pos = "", 0
     while True:
         i = text.find("<<<", pos)

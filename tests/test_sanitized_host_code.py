@@ -64,6 +64,9 @@ KERNEL_CASES = [
     (4, 2, 4, 6, 64, 0, 1, 8, 4),         # the paper's four-job schedule
     (5, 2, 10, 6, 30, 1, 1, 8, 4),        # ten jobs, c = 2, two-element alignment only
     (4, 2, 4, 240, 12, 0, 0, 8, 4),       # 40 files a batch: wavefront-wide combiner
+    (10, 3, 10, 120, 512, 0, 0, 256, 5),  # the 10-node plan, ragged split, chunked as on the device
+    (8, 2, 8, 28, 4096, 3, 0, 1, 1),      # the gradient shape's plan, bfloat16, a single chunk, several column tiles
+    (8, 4, 8, 70, 2048, 1, 0, 256, 3),    # r = 4 with the many-node shape's value length: two-element packs
 ]
 
 
